@@ -1,0 +1,122 @@
+/*
+ * varlen_attn.h — C ABI of the MI355X (gfx950) document-masked causal attention library.
+ *
+ * The operation (Section 5.2, "Micro-Batch Time Prediction"): a packed micro-batch holds
+ * documents of lengths l_1..l_k, sum N, concatenated along the token axis; a
+ * block-diagonal mask keeps attention inside each document, so the cost follows
+ * sum_i l_i^2 (Eq. 1) instead of N^2.  The models are decoder-only, so the mask is causal
+ * inside each block: token t of document b attends to keys j with cu[b] <= j <= t.
+ *
+ *   forward :  S = scale * Q K^T (masked),  LSE = log sum exp S,  P = exp(S - LSE),  O = P V
+ *   backward:  D = rowsum(dO * O),  dV = P^T dO,  dP = dO V^T,  dS = P * (dP - D),
+ *              dQ = scale * dS K,   dK = scale * dS^T Q      (P recomputed from LSE)
+ *
+ * Grouped-query attention: q-head h reads kv-head h / (num_q_heads / num_kv_heads);
+ * dK and dV are summed over the q-heads of each group.
+ *
+ * Memory: every pointer below except `params` is a DEVICE pointer owned by the caller,
+ * 16-byte aligned.  The library allocates nothing, keeps no state between calls and never
+ * synchronises with the host (varlen_attn_check excepted); all work is enqueued on
+ * `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *
+ * Layouts (row-major, contiguous):
+ *   q, o, d_o, dq : bf16 [N, num_q_heads,  head_dim]
+ *   k, v, dk, dv  : bf16 [N, num_kv_heads, head_dim]
+ *   lse           : fp32 [num_q_heads, N]   natural log of sum_j exp(scale * q.k_j)
+ *   cu_seqlens    : int32 [num_docs + 1], cu[0] = 0, cu[num_docs] = N, non-decreasing;
+ *                   document b owns tokens cu[b] .. cu[b+1]-1; empty documents are legal.
+ * Outputs are fully overwritten.  A malformed cu_seqlens is detected on the device: the
+ * plan then holds no work items, no output is written, and varlen_attn_check reports it.
+ */
+#ifndef VARLEN_ATTN_H_
+#define VARLEN_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Tile geometry of the plan: every non-empty document is cut into tiles of
+ * VARLEN_ATTN_TILE_ROWS consecutive tokens starting at its first token. */
+#define VARLEN_ATTN_TILE_ROWS 128
+
+/* Status codes (0 = success, negative = error). */
+#define VARLEN_ATTN_OK 0
+#define VARLEN_ATTN_INVALID_ARG (-1)          /* null pointer, non-positive size, Hq % Hkv != 0, bad scale */
+#define VARLEN_ATTN_UNSUPPORTED (-2)          /* head_dim not in {64,128}, misaligned pointer */
+#define VARLEN_ATTN_WORKSPACE_TOO_SMALL (-3)
+#define VARLEN_ATTN_LAUNCH_FAILED (-4)        /* the HIP runtime refused a launch */
+#define VARLEN_ATTN_BAD_CU_SEQLENS (-5)       /* reported by varlen_attn_check only */
+
+/* flags */
+#define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* bwd only: the workspace still holds the plan that a
+                                         preceding varlen_attn_fwd / varlen_attn_plan call
+                                         with the same params and cu_seqlens wrote */
+
+typedef struct {
+  int32_t total_tokens;  /* N   >= 1 */
+  int32_t num_docs;      /* B   >= 1; cu_seqlens has B + 1 entries */
+  int32_t num_q_heads;   /* Hq  >= 1 */
+  int32_t num_kv_heads;  /* Hkv >= 1, Hq % Hkv == 0 */
+  int32_t head_dim;      /* 64 or 128 */
+  float softmax_scale;   /* finite, > 0 (usually 1/sqrt(head_dim)) */
+  int32_t flags;         /* VARLEN_ATTN_FLAG_* */
+} varlen_attn_params;
+
+/* Work item of the plan: one tile of one document.  Items are ordered by non-increasing
+ * cost (number of tiles at or below it in its document), i.e. longest job first. */
+typedef struct {
+  int32_t row0;      /* first token of the tile */
+  int32_t doc_start; /* cu[b]   */
+  int32_t doc_end;   /* cu[b+1] */
+  int32_t cost;      /* tile index inside the document + 1 */
+} varlen_attn_item;
+
+/* Header at the start of the workspace, written by the plan step. */
+typedef struct {
+  int32_t n_items;   /* number of work items that follow */
+  int32_t status;    /* VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS */
+  int64_t pairs;     /* sum_b l_b (l_b + 1) / 2: (query, key) pairs inside the mask */
+  int32_t max_items; /* capacity of the item array: N / TILE_ROWS + B */
+  int32_t reserved[3];
+} varlen_attn_plan_header;
+
+/* Workspace layout: [plan header][max_items items][fp32 D, Hq * N (backward only)].
+ * Bytes the caller must provide (device memory, 16-byte aligned); 0 if params are invalid.
+ * Host function, no device work. */
+size_t varlen_attn_workspace_bytes(const varlen_attn_params* params);
+
+/* Byte offset of the item array inside the workspace (host function). */
+size_t varlen_attn_workspace_items_offset(const varlen_attn_params* params);
+
+/* Plan step alone (it is also the first step of varlen_attn_fwd and, unless
+ * VARLEN_ATTN_FLAG_REUSE_PLAN is set, of varlen_attn_bwd): reads cu_seqlens on the device,
+ * validates it, and writes header + items into the workspace.  Integer work only. */
+int varlen_attn_plan(const varlen_attn_params* params, const int32_t* cu_seqlens,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Forward: writes o and lse. */
+int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void* k,
+                    const void* v, const int32_t* cu_seqlens, void* o, float* lse,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward: reads q, k, v, o, lse (as written by the forward) and d_o; writes dq, dk, dv.
+ * Deterministic: no atomics on floating-point data, results are bit-reproducible. */
+int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void* k,
+                    const void* v, const void* o, const float* lse, const void* d_o,
+                    const int32_t* cu_seqlens, void* dq, void* dk, void* dv, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* Synchronises `hip_stream` and returns the status word the last plan step left in the
+ * workspace (VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS).  The only call that blocks. */
+int varlen_attn_check(const void* workspace, void* hip_stream);
+
+/* Static text for a status code; never NULL. */
+const char* varlen_attn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARLEN_ATTN_H_ */

@@ -1,0 +1,142 @@
+"""ctypes binding of libvarlen_attn.so (argument marshalling only).
+
+Function names and argument order follow include/varlen_attn.h.  Tensor arguments may be
+torch tensors (their ``data_ptr()`` is passed) or raw integer device addresses.  PyTorch is
+used by callers for device memory and streams; no arithmetic happens on this side, and
+there is no fallback: a missing library is an ImportError-like failure at first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libvarlen_attn.so")
+
+TILE_ROWS = 128
+OK = 0
+INVALID_ARG = -1
+UNSUPPORTED = -2
+WORKSPACE_TOO_SMALL = -3
+LAUNCH_FAILED = -4
+BAD_CU_SEQLENS = -5
+FLAG_REUSE_PLAN = 1
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("total_tokens", ctypes.c_int32), ("num_docs", ctypes.c_int32),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("flags", ctypes.c_int32)]
+
+
+class PlanHeader(ctypes.Structure):
+    _fields_ = [("n_items", ctypes.c_int32), ("status", ctypes.c_int32),
+                ("pairs", ctypes.c_int64), ("max_items", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 3)]
+
+
+class Item(ctypes.Structure):
+    _fields_ = [("row0", ctypes.c_int32), ("doc_start", ctypes.c_int32),
+                ("doc_end", ctypes.c_int32), ("cost", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_06374_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, pp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(Params)
+        L.varlen_attn_workspace_bytes.restype = sz
+        L.varlen_attn_workspace_bytes.argtypes = [pp]
+        L.varlen_attn_workspace_items_offset.restype = sz
+        L.varlen_attn_workspace_items_offset.argtypes = [pp]
+        L.varlen_attn_plan.restype = ctypes.c_int
+        L.varlen_attn_plan.argtypes = [pp, vp, vp, sz, vp]
+        L.varlen_attn_fwd.restype = ctypes.c_int
+        L.varlen_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.varlen_attn_bwd.restype = ctypes.c_int
+        L.varlen_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.varlen_attn_check.restype = ctypes.c_int
+        L.varlen_attn_check.argtypes = [vp, vp]
+        L.varlen_attn_status_string.restype = ctypes.c_char_p
+        L.varlen_attn_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def make_params(total_tokens, num_docs, num_q_heads, num_kv_heads, head_dim, softmax_scale,
+                flags=0) -> Params:
+    return Params(int(total_tokens), int(num_docs), int(num_q_heads), int(num_kv_heads),
+                  int(head_dim), float(softmax_scale), int(flags))
+
+
+def _addr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _nbytes(x, given) -> int:
+    if given is not None:
+        return int(given)
+    return int(x.numel() * x.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def varlen_attn_workspace_bytes(params: Params) -> int:
+    return int(lib().varlen_attn_workspace_bytes(ctypes.byref(params)))
+
+
+def varlen_attn_workspace_items_offset(params: Params) -> int:
+    return int(lib().varlen_attn_workspace_items_offset(ctypes.byref(params)))
+
+
+def varlen_attn_plan(params, cu_seqlens, workspace, workspace_bytes=None, stream=None) -> int:
+    return int(lib().varlen_attn_plan(ctypes.byref(params), _addr(cu_seqlens), _addr(workspace),
+                                      _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def varlen_attn_fwd(params, q, k, v, cu_seqlens, o, lse, workspace, workspace_bytes=None,
+                    stream=None) -> int:
+    return int(lib().varlen_attn_fwd(ctypes.byref(params), _addr(q), _addr(k), _addr(v),
+                                     _addr(cu_seqlens), _addr(o), _addr(lse), _addr(workspace),
+                                     _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def varlen_attn_bwd(params, q, k, v, o, lse, d_o, cu_seqlens, dq, dk, dv, workspace,
+                    workspace_bytes=None, stream=None) -> int:
+    return int(lib().varlen_attn_bwd(ctypes.byref(params), _addr(q), _addr(k), _addr(v), _addr(o),
+                                     _addr(lse), _addr(d_o), _addr(cu_seqlens), _addr(dq),
+                                     _addr(dk), _addr(dv), _addr(workspace),
+                                     _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def varlen_attn_check(workspace, stream=None) -> int:
+    return int(lib().varlen_attn_check(_addr(workspace), _stream(stream)))
+
+
+def varlen_attn_status_string(status: int) -> str:
+    return lib().varlen_attn_status_string(int(status)).decode()
+
+
+def check(status: int) -> None:
+    if status != OK:
+        raise RuntimeError(f"varlen_attn: {varlen_attn_status_string(status)} ({status})")

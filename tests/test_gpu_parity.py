@@ -1,0 +1,265 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU fp64 oracle, element by
+element on the same seeded inputs.  Tolerances: max|x-y|/max|y| <= 1e-2 for O, 2e-2 for
+dQ/dK/dV; LSE within 1e-3 * max(1, |y|); integer/plan work bit-exact."""
+import math
+
+import numpy as np
+import pytest
+
+from helpers import (TOL_GRAD, TOL_LSE, TOL_O, assert_close_full, e1, f64_values,
+                     interesting_rows, key_rows_cheap, oracle_full, oracle_keys, oracle_rows)
+from oracle import plan as oplan
+from paper_2605_06374_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2605_06374_amd import binding, runner
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.lib()   # fail loudly if the HIP library is missing
+    return runner
+
+
+def run_all(gpu, w, values=None, poison=True):
+    from paper_2605_06374_amd import binding
+    prob = gpu.DeviceProblem(w, values=values)
+    if poison:
+        prob.poison_outputs()
+    prob.forward()
+    prob.backward(reuse_plan=True)
+    assert binding.varlen_attn_check(prob.workspace) == binding.OK
+    return prob
+
+
+SMALL = [
+    # lengths, Hq, Hkv, d
+    ([1], 1, 1, 64),
+    ([1], 2, 1, 128),
+    ([5], 2, 2, 128),
+    ([31, 32, 33], 2, 2, 64),
+    ([63, 64, 65], 2, 1, 128),
+    ([127, 128, 129], 4, 2, 128),
+    ([64, 300, 1, 515], 4, 4, 128),
+    ([64, 300, 1, 515], 4, 2, 64),
+    ([1] * 40, 2, 2, 128),
+    ([200, 0, 0, 77, 0], 2, 1, 128),          # empty documents
+    ([0, 130], 1, 1, 64),
+    ([1000], 3, 3, 128),                      # B = 1, odd head count
+    ([257, 511, 769], 8, 1, 128),             # 8:1 GQA
+    ([16, 17, 18, 19, 20] * 8, 4, 4, 128),
+    ([1537], 2, 2, 64),
+]
+
+
+@pytest.mark.parametrize("lengths,hq,hkv,d", SMALL)
+def test_small_shapes_full_parity(gpu, lengths, hq, hkv, d):
+    print(f"case lengths={lengths[:8]} hq={hq} hkv={hkv} d={d}", flush=True)
+    w = W.custom("small", lengths, hq, hkv, d, seed=sum(lengths) + 13 * hq + d)
+    prob = run_all(gpu, w)
+    errs = assert_close_full(prob.results(), oracle_full(w), label=str(lengths[:6]))
+    print("  errors (E1, E2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
+
+
+def test_non_default_scale_and_std(gpu):
+    w = W.custom("scaled", [300, 45, 700], 4, 2, 128, std=0.5, seed=5)
+    w.__class__ = type("WS", (W.Workload,), {"softmax_scale": property(lambda self: 0.21)})
+    prob = run_all(gpu, w)
+    assert_close_full(prob.results(), oracle_full(w), "scale 0.21")
+
+
+def test_config1_tiny_full(gpu):
+    w = W.config(1)
+    prob = run_all(gpu, w)
+    errs = assert_close_full(prob.results(), oracle_full(w), "cfg1")
+    print("cfg1 errors:", errs, flush=True)
+
+
+def test_config2_7b_shard_full(gpu):
+    w = W.config(2)
+    prob = run_all(gpu, w)
+    errs = assert_close_full(prob.results(), oracle_full(w), "cfg2")
+    print("cfg2 errors:", errs, flush=True)
+
+
+def _sampled_parity(gpu, w, n_rows, n_keys, seed):
+    prob = run_all(gpu, w)
+    got = prob.results()
+    for name in ("o", "dq", "dk", "dv", "lse"):
+        assert np.isfinite(got[name]).all(), f"{w.name} {name}: non-finite (unwritten?) output"
+    rng = np.random.default_rng(seed)
+    rows = interesting_rows(w.cu_seqlens, n_rows, rng)
+    ref = oracle_rows(w, rows)
+    print(f"{w.name}: {len(rows)} sampled query rows", flush=True)
+    # the scale of each tensor is taken from the oracle's sampled rows
+    assert np.abs(got["o"][rows] - ref["o"]).max() <= TOL_O * np.abs(ref["o"]).max()
+    assert np.abs(got["dq"][rows] - ref["dq"]).max() <= TOL_GRAD * np.abs(ref["dq"]).max()
+    dl = np.abs(got["lse"][:, rows] - ref["lse"]) / np.maximum(1.0, np.abs(ref["lse"]))
+    assert dl.max() <= TOL_LSE
+    keys = key_rows_cheap(w.cu_seqlens, n_keys, rng)
+    refk = oracle_keys(w, keys)
+    print(f"{w.name}: {len(keys)} sampled key rows", flush=True)
+    assert np.abs(got["dk"][keys] - refk["dk"]).max() <= TOL_GRAD * np.abs(refk["dk"]).max()
+    assert np.abs(got["dv"][keys] - refk["dv"]).max() <= TOL_GRAD * np.abs(refk["dv"]).max()
+    # properties that hold at any size (from the inputs alone):
+    #   sum_j dV[j, kappa] = sum_{t, h in group} dO[t, h]  per document;  sum_j dK[j] = 0
+    v = f64_values(w)
+    cu = w.cu_seqlens
+    g = w.n_q_heads // w.n_kv_heads
+    for b in range(len(cu) - 1):
+        s, e = int(cu[b]), int(cu[b + 1])
+        if e == s:
+            continue
+        want = v["do"][s:e].reshape(e - s, w.n_kv_heads, g, w.head_dim).sum(axis=(0, 2))
+        gotv = got["dv"][s:e].sum(axis=0)
+        scale_v = np.abs(got["dv"][s:e]).sum(axis=0).max()
+        assert np.abs(gotv - want).max() <= 4e-3 * scale_v + 1e-6, (b, "dV column sums")
+        scale_k = np.abs(got["dk"][s:e]).sum(axis=0).max()
+        assert np.abs(got["dk"][s:e].sum(axis=0)).max() <= 4e-3 * scale_k + 1e-6, (b, "dK sums")
+    return prob
+
+
+def test_config3_longtail_sampled(gpu):
+    _sampled_parity(gpu, W.config(3), n_rows=48, n_keys=48, seed=303)
+
+
+def test_config4_gqa_sampled(gpu):
+    _sampled_parity(gpu, W.config(4), n_rows=64, n_keys=64, seed=404)
+
+
+@pytest.mark.parametrize("mb", [0, 1, 5, 8, 63])
+def test_config5_sweep_microbatches(gpu, mb):
+    w = W.config(5, microbatch=mb)
+    if w.pairs <= 3_000_000:
+        prob = run_all(gpu, w)
+        assert_close_full(prob.results(), oracle_full(w), w.name)
+    else:
+        _sampled_parity(gpu, w, n_rows=48, n_keys=48, seed=500 + mb)
+
+
+def test_mid_size_long_document_full(gpu):
+    """A 3000-token document next to short ones: every dK/dV row of a long document checked."""
+    w = W.custom("mid", [3000, 17, 600, 479], 4, 2, 128, seed=77)
+    prob = run_all(gpu, w)
+    assert_close_full(prob.results(), oracle_full(w), "mid")
+
+
+# ------------------------------------------------------------------ cu_seqlens handling, bit-exact
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_plan_integers_match_oracle(gpu, k):
+    w = W.config(k)
+    prob = gpu.DeviceProblem(w)
+    prob.plan()
+    hdr, items = prob.read_plan()
+    cu = w.cu_seqlens
+    assert hdr.status == 0 and hdr.pairs == oplan.pairs(cu) == w.pairs
+    want = oplan.row_tiles(cu, 128)
+    assert hdr.n_items == len(want)
+    got = sorted((int(r0), int(s), int(e), int(c)) for r0, s, e, c in items)
+    ref = sorted((r0, int(cu[b]), int(cu[b + 1]), i + 1) for b, i, r0, _ in want)
+    assert got == ref
+    costs = items[:, 3]
+    assert (np.diff(costs) <= 0).all(), "items must be ordered longest job first"
+
+
+def test_plan_many_short_documents(gpu):
+    lengths = [1 + (i * 7) % 40 for i in range(3000)]
+    w = W.custom("many", lengths, 1, 1, 64, seed=1)
+    prob = gpu.DeviceProblem(w)
+    prob.plan()
+    hdr, items = prob.read_plan()
+    want = oplan.row_tiles(w.cu_seqlens, 128)
+    assert hdr.n_items == len(want) and hdr.pairs == w.pairs
+    assert sorted(int(x) for x in items[:, 0]) == sorted(r0 for _, _, r0, _ in want)
+
+
+def test_bad_cu_seqlens_is_reported_and_writes_nothing(gpu):
+    import torch
+    from paper_2605_06374_amd import binding
+    w = W.custom("bad", [100, 200, 84], 2, 2, 128, seed=3)
+    for bad in ([0, 250, 200, 384], [1, 100, 300, 384], [0, 100, 300, 383]):
+        prob = gpu.DeviceProblem(w)
+        prob.cu.copy_(torch.tensor(bad, dtype=torch.int32))
+        prob.poison_outputs()
+        prob.forward()
+        prob.backward()
+        assert binding.varlen_attn_check(prob.workspace) == binding.BAD_CU_SEQLENS
+        bits = prob.result_bits()
+        assert (bits["o"] == 0x7FC0).all() and (bits["dq"] == 0x7FC0).all()
+        assert (bits["dk"] == 0x7FC0).all() and (bits["dv"] == 0x7FC0).all()
+
+
+def test_first_row_identity(gpu):
+    """The first token of a document sees one key: P = 1, so O equals its V row bit for bit,
+    LSE = scale * q.k, and dQ vanishes."""
+    w = W.config(2)
+    prob = run_all(gpu, w)
+    bits = prob.result_bits()
+    vals = w.values()
+    got = prob.results()
+    v64 = f64_values(w)
+    g = w.n_q_heads // w.n_kv_heads
+    for b in range(len(w.lengths)):
+        t = int(w.cu_seqlens[b])
+        for h in range(w.n_q_heads):
+            assert np.array_equal(bits["o"][t, h], vals["v"][t, h // g])
+            s = w.softmax_scale * float(v64["q"][t, h] @ v64["k"][t, h // g])
+            assert abs(got["lse"][h, t] - s) <= 2e-6 * max(1.0, abs(s))
+            assert np.abs(got["dq"][t, h]).max() <= 1e-5 * w.softmax_scale * np.abs(v64["k"][t]).max() * 10
+
+
+def test_isolation_and_packing_invariance_bit_exact(gpu):
+    """(i) poisoning every token outside a document leaves that document's outputs
+    bit-identical; (ii) a document run alone gives the same bits as inside the pack."""
+    w = W.custom("iso", [300, 130, 1, 700, 64], 4, 2, 128, seed=9)
+    vals = w.values()
+    base = run_all(gpu, w).result_bits()
+    cu = w.cu_seqlens
+    for b in (0, 1, 2, 3):
+        s, e = int(cu[b]), int(cu[b + 1])
+        poisoned = {}
+        for n, x in vals.items():
+            y = x.copy()
+            y[:s] = 0x7FC0 if n != "k" else 0x7F80     # NaN, and +Inf in K
+            y[e:] = 0x7FC0 if n != "v" else 0x7E00     # NaN, and huge in V
+            poisoned[n] = y
+        got = run_all(gpu, w, values=poisoned).result_bits()
+        for n in ("o", "dq", "dk", "dv"):
+            assert np.array_equal(got[n][s:e], base[n][s:e]), (b, n)
+        assert np.array_equal(got["lse"][:, s:e], base["lse"][:, s:e])
+        alone = W.custom("alone", [e - s], 4, 2, 128, seed=0)
+        alone_vals = {n: x[s:e].copy() for n, x in vals.items()}
+        got1 = run_all(gpu, alone, values=alone_vals).result_bits()
+        for n in ("o", "dq", "dk", "dv"):
+            assert np.array_equal(got1[n], base[n][s:e]), (b, n, "alone")
+        assert np.array_equal(got1["lse"], base["lse"][:, s:e])
+
+
+def test_bit_reproducible(gpu):
+    w = W.config(4)
+    a = run_all(gpu, w).result_bits()
+    b = run_all(gpu, w).result_bits()
+    for n in a:
+        assert np.array_equal(a[n], b[n]), n
+
+
+def test_bwd_plans_itself_without_reuse_flag(gpu):
+    from paper_2605_06374_amd import binding
+    w = W.custom("noreuse", [500, 77], 2, 2, 128, seed=21)
+    prob = gpu.DeviceProblem(w)
+    prob.poison_outputs()
+    prob.forward()
+    prob.workspace.zero_()          # wipe the plan: bwd must rebuild it
+    prob.backward(reuse_plan=False)
+    assert binding.varlen_attn_check(prob.workspace) == binding.OK
+    assert_close_full(prob.results(), oracle_full(w), "noreuse")
+
+
+def test_cost_follows_sum_of_squares_not_n_squared(gpu):
+    """Section 2.2: one 4K document costs about four times four packed 1K documents; the
+    tile pairs the kernels visit follow the same ratio (tile skipping)."""
+    a = oplan.causal_tile_pairs([0, 4096], 128, 64)
+    b = oplan.causal_tile_pairs([0, 1024, 2048, 3072, 4096], 128, 64)
+    assert 3.5 < a / b < 4.0
