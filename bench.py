@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one step = plan + forward + backward of document-masked causal
+attention over one packed microbatch (the 8K-token 7B-style TP=8 shard by default), inputs
+resident in HBM, on ONE MI355X.
+
+Prints one JSON line: whole-job TFLOP/s by the causal per-document FLOP count
+14 * d * Hq * sum_b l_b (l_b + 1) / 2, the roofline position of the dominant kernel (timed
+live with HIP events on the launch stream), and the CPU fp64 oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "fwd+bwd causal attention TFLOP/s and % of bf16 MFMA peak per packed microbatch"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured for the workload being run.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..4")
+    ap.add_argument("--buffers", type=int, default=4,
+                    help="buffer sets rotated through (4 x 109 MB exceeds the 256 MB Infinity Cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_06374_amd import binding, workloads as W
+    from paper_2605_06374_amd.runner import DeviceProblem
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    binding.lib()  # fails loudly when the HIP library is missing
+
+    w = W.config(args.config)
+    vals = w.values()
+    probs = [DeviceProblem(w, values=vals) for _ in range(max(1, args.buffers))]
+
+    def step(i):
+        p = probs[i % len(probs)]
+        p.forward()
+        p.backward(reuse_plan=True)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for p in probs:
+        assert binding.varlen_attn_check(p.workspace) == binding.OK
+    sec_per_step = (t1 - t0) / args.steps
+    flops = w.flops_fwd_bwd
+    tflops = flops / sec_per_step / 1e12
+
+    # ---- per-kernel durations: same steps again, each launch bracketed by HIP events
+    kernels = {}
+    roofline = None
+    if not args.no_kernel_timing:
+        binding.varlen_attn_profile(True)
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        rec = binding.varlen_attn_profile_read()
+        binding.varlen_attn_profile(False)
+        kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in rec.items()}
+        # algorithmic flops per launch: 2*d per (pair, contraction); forward S and PV;
+        # dK/dV kernel S, dP, dV, dK; dQ kernel only the dQ contraction is new work
+        per_pair = {"fwd_kernel": 4, "bwd_dkv_kernel": 8, "bwd_dq_kernel": 2}
+        dom = max((k for k in kernels if k in per_pair), key=lambda k: kernels[k]["avg_us"])
+        alg = per_pair[dom] * w.head_dim * w.n_q_heads * w.pairs
+        achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "algorithmic_flops_per_launch": alg,
+                    "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
+
+    # ---- CPU oracle on the host cores (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import attention as oracle
+        v64 = {n: W.bf16_bits_to_f32(b).astype(np.float64) for n, b in vals.items()}
+        threads = oracle.set_threads(0)
+        c0 = time.perf_counter()
+        oracle.fwd(v64["q"], v64["k"], v64["v"], w.cu_seqlens, w.softmax_scale)
+        oracle.bwd(v64["q"], v64["k"], v64["v"], v64["do"], w.cu_seqlens, w.softmax_scale)
+        c1 = time.perf_counter()
+        cpu = {"value": round(flops / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
+               "kind": "oracle", "seconds": round(c1 - c0, 2),
+               "sample": f"one full {w.name} microbatch, forward + backward, once"}
+
+    props = torch.cuda.get_device_properties(0)
+    out = {
+        "metric": METRIC,
+        "value": round(tflops, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "tokens": w.n_tokens, "docs": len(w.lengths),
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "pairs": w.pairs, "flops_per_step": flops, "buffer_sets": len(probs),
+                   "step": "plan + fwd + bwd"},
+        "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_GBps": round(w.algorithmic_bytes / sec_per_step / 1e9, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in kernels.items()},
+        "device": {"name": props.name, "cus": props.multi_processor_count},
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

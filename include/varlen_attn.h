@@ -113,6 +113,23 @@ int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void*
  * workspace (VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS).  The only call that blocks. */
 int varlen_attn_check(const void* workspace, void* hip_stream);
 
+/* Optional per-kernel timing for benchmarks.  While enabled (enable != 0), every kernel
+ * launch made by this library is bracketed by two HIP events recorded on the launch's own
+ * stream (host-side objects; no device memory).  Calling it again, with either value,
+ * drops the records collected so far.  Off by default; not thread-safe against concurrent
+ * launches that should not be timed. */
+typedef struct {
+  const char* name; /* static string, e.g. "bwd_dkv_kernel" */
+  int32_t launches; /* number of launches recorded */
+  float total_ms;   /* sum of their durations */
+} varlen_attn_kernel_time;
+int varlen_attn_profile(int enable);
+
+/* Waits for the recorded events, writes one entry per kernel that was launched (at most
+ * `capacity`), clears the records and returns the number of entries, or a negative status.
+ * Blocks the host. */
+int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity);
+
 /* Static text for a status code; never NULL. */
 const char* varlen_attn_status_string(int status);
 

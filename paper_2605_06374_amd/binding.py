@@ -37,6 +37,11 @@ class PlanHeader(ctypes.Structure):
                 ("reserved", ctypes.c_int32 * 3)]
 
 
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int32),
+                ("total_ms", ctypes.c_float)]
+
+
 class Item(ctypes.Structure):
     _fields_ = [("row0", ctypes.c_int32), ("doc_start", ctypes.c_int32),
                 ("doc_end", ctypes.c_int32), ("cost", ctypes.c_int32)]
@@ -68,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.varlen_attn_check.argtypes = [vp, vp]
         L.varlen_attn_status_string.restype = ctypes.c_char_p
         L.varlen_attn_status_string.argtypes = [ctypes.c_int]
+        L.varlen_attn_profile.restype = ctypes.c_int
+        L.varlen_attn_profile.argtypes = [ctypes.c_int]
+        L.varlen_attn_profile_read.restype = ctypes.c_int
+        L.varlen_attn_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int]
         _lib = L
     return _lib
 
@@ -131,6 +140,18 @@ def varlen_attn_bwd(params, q, k, v, o, lse, d_o, cu_seqlens, dq, dk, dv, worksp
 
 def varlen_attn_check(workspace, stream=None) -> int:
     return int(lib().varlen_attn_check(_addr(workspace), _stream(stream)))
+
+
+def varlen_attn_profile(enable: bool) -> int:
+    return int(lib().varlen_attn_profile(1 if enable else 0))
+
+
+def varlen_attn_profile_read():
+    """{kernel name: (launches, total_ms)} of the launches recorded since profiling was enabled."""
+    buf = (KernelTime * 16)()
+    n = int(lib().varlen_attn_profile_read(buf, 16))
+    check(min(n, 0))
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n)}
 
 
 def varlen_attn_status_string(status: int) -> str:

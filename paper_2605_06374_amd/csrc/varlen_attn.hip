@@ -19,6 +19,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <vector>
+
 #include "varlen_attn.h"
 
 namespace {
@@ -696,6 +699,44 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 // ----------------------------------------------------------------------------------------
 // Host side
 // ----------------------------------------------------------------------------------------
+
+// ----------------------------------------------------------------------------------------
+// Optional per-kernel timing (host-side HIP events only; off by default).
+// ----------------------------------------------------------------------------------------
+enum KernelId { kPlan = 0, kFwd, kRowdot, kDkv, kDq, kNumKernels };
+const char* const kKernelNames[kNumKernels] = {"plan_kernel", "fwd_kernel", "rowdot_kernel",
+                                               "bwd_dkv_kernel", "bwd_dq_kernel"};
+struct Profiler {
+  std::mutex mu;
+  bool enabled = false;
+  struct Rec { int id; hipEvent_t start, stop; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Profiler& profiler() { static Profiler p; return p; }
+
+// Brackets one launch with events when profiling is on.
+struct ScopedKernelTimer {
+  hipStream_t stream; hipEvent_t stop = nullptr;
+  ScopedKernelTimer(int id, hipStream_t s) : stream(s) {
+    Profiler& p = profiler();
+    if (!p.enabled) return;
+    std::lock_guard<std::mutex> g(p.mu);
+    hipEvent_t start = p.get();
+    stop = p.get();
+    if (!start || !stop) { stop = nullptr; return; }
+    (void)hipEventRecord(start, stream);
+    p.recs.push_back({id, start, stop});
+  }
+  ~ScopedKernelTimer() { if (stop) (void)hipEventRecord(stop, stream); }
+};
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
@@ -744,10 +785,39 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, char* ws, const 
   int shift = 0;
   const int max_cost = (p->total_tokens + kTile - 1) / kTile;
   while ((max_cost - 1) >> shift >= kPlanBins) ++shift;
+  ScopedKernelTimer timer(kPlan, stream);
   plan_kernel<<<1, kPlanThreads, 0, stream>>>(
       cu, p->num_docs, p->total_tokens, shift, reinterpret_cast<varlen_attn_plan_header*>(ws),
       reinterpret_cast<varlen_attn_item*>(ws + L.items_off), L.max_items);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
+}
+
+template <int D>
+void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const void* v,
+                const void* o, const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                const varlen_attn_plan_header* hdr, const varlen_attn_item* items, float* dsum,
+                const Layout& L, hipStream_t stream) {
+  const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
+  const float scale = p->softmax_scale;
+  const long long rows = (long long)N * Hq;
+  constexpr int kRowsPerBlock = kThreads / (D / 8);
+  {
+    ScopedKernelTimer timer(kRowdot, stream);
+    rowdot_kernel<D><<<(unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), kThreads, 0, stream>>>(
+        (const __bf16*)o, (const __bf16*)d_o, dsum, N, Hq);
+  }
+  {
+    ScopedKernelTimer timer(kDkv, stream);
+    bwd_dkv_kernel<D><<<dim3((unsigned)L.max_items * Hkv), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
+        items, (__bf16*)dk, (__bf16*)dv, N, Hq, Hkv, scale);
+  }
+  {
+    ScopedKernelTimer timer(kDq, stream);
+    bwd_dq_kernel<D><<<dim3((unsigned)L.max_items * Hq), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
+        items, (__bf16*)dq, N, Hq, Hkv, scale);
+  }
 }
 
 }  // namespace
@@ -792,6 +862,7 @@ int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void*
   const auto* items = reinterpret_cast<const varlen_attn_item*>(ws + L.items_off);
   const int N = params->total_tokens, Hq = params->num_q_heads, Hkv = params->num_kv_heads;
   const dim3 grid((unsigned)L.max_items * Hq);
+  ScopedKernelTimer timer(kFwd, stream);
   if (params->head_dim == 128)
     fwd_kernel<128><<<grid, kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, hdr, items, (__bf16*)o, lse, N, Hq,
@@ -820,28 +891,10 @@ int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void*
   const auto* hdr = reinterpret_cast<const varlen_attn_plan_header*>(ws);
   const auto* items = reinterpret_cast<const varlen_attn_item*>(ws + L.items_off);
   float* dsum = reinterpret_cast<float*>(ws + L.dsum_off);
-  const int N = params->total_tokens, Hq = params->num_q_heads, Hkv = params->num_kv_heads;
-  const float scale = params->softmax_scale;
-  const long long rows = (long long)N * Hq;
-  if (params->head_dim == 128) {
-    const unsigned rgrid = (unsigned)((rows + kThreads / 16 - 1) / (kThreads / 16));
-    rowdot_kernel<128><<<rgrid, kThreads, 0, stream>>>((const __bf16*)o, (const __bf16*)d_o, dsum, N, Hq);
-    bwd_dkv_kernel<128><<<dim3((unsigned)L.max_items * Hkv), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dk, (__bf16*)dv, N, Hq, Hkv, scale);
-    bwd_dq_kernel<128><<<dim3((unsigned)L.max_items * Hq), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dq, N, Hq, Hkv, scale);
-  } else {
-    const unsigned rgrid = (unsigned)((rows + kThreads / 8 - 1) / (kThreads / 8));
-    rowdot_kernel<64><<<rgrid, kThreads, 0, stream>>>((const __bf16*)o, (const __bf16*)d_o, dsum, N, Hq);
-    bwd_dkv_kernel<64><<<dim3((unsigned)L.max_items * Hkv), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dk, (__bf16*)dv, N, Hq, Hkv, scale);
-    bwd_dq_kernel<64><<<dim3((unsigned)L.max_items * Hq), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dq, N, Hq, Hkv, scale);
-  }
+  if (params->head_dim == 128)
+    launch_bwd<128>(params, q, k, v, o, lse, d_o, dq, dk, dv, hdr, items, dsum, L, stream);
+  else
+    launch_bwd<64>(params, q, k, v, o, lse, d_o, dq, dk, dv, hdr, items, dsum, L, stream);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
@@ -853,6 +906,42 @@ int varlen_attn_check(const void* workspace, void* hip_stream) {
     return VARLEN_ATTN_LAUNCH_FAILED;
   if (hipStreamSynchronize(stream) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
   return hdr.status;
+}
+
+int varlen_attn_profile(int enable) {
+  Profiler& p = profiler();
+  std::lock_guard<std::mutex> g(p.mu);
+  for (auto& r : p.recs) { p.pool.push_back(r.start); p.pool.push_back(r.stop); }
+  p.recs.clear();
+  p.enabled = enable != 0;
+  return VARLEN_ATTN_OK;
+}
+
+int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity) {
+  if (!out || capacity < 1) return VARLEN_ATTN_INVALID_ARG;
+  Profiler& p = profiler();
+  std::lock_guard<std::mutex> g(p.mu);
+  float total[kNumKernels] = {0};
+  int count[kNumKernels] = {0};
+  for (auto& r : p.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+      return VARLEN_ATTN_LAUNCH_FAILED;
+    total[r.id] += ms;
+    count[r.id] += 1;
+    p.pool.push_back(r.start);
+    p.pool.push_back(r.stop);
+  }
+  p.recs.clear();
+  int n = 0;
+  for (int i = 0; i < kNumKernels && n < capacity; ++i) {
+    if (!count[i]) continue;
+    out[n].name = kKernelNames[i];
+    out[n].launches = count[i];
+    out[n].total_ms = total[i];
+    ++n;
+  }
+  return n;
 }
 
 const char* varlen_attn_status_string(int status) {
