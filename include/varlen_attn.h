@@ -38,9 +38,18 @@
 extern "C" {
 #endif
 
-/* Tile geometry of the plan: every non-empty document is cut into tiles of
- * VARLEN_ATTN_TILE_ROWS consecutive tokens starting at its first token. */
+/* Geometry of the plan.  Every non-empty document is cut into tiles of
+ * VARLEN_ATTN_TILE_ROWS consecutive tokens starting at its first token.  The work of a tile
+ * is a chain of steps of VARLEN_ATTN_STEP_ROWS rows each:
+ *   row chain (forward, dQ):  key steps 0 .. ceil((last valid row of the tile + 1 - cu[b]) / 64) - 1,
+ *                             step s holding keys cu[b] + 64 s .. + 63;
+ *   column chain (dK, dV):    query steps 0 .. ceil((cu[b+1] - row0) / 64) - 1,
+ *                             step s holding queries row0 + 64 s .. + 63.
+ * A long chain is cut into chunks of nearly equal length so that a short microbatch still
+ * fills the GPU; each chunk is one work unit, and the partial results of a cut chain are
+ * summed afterwards in a fixed order (deterministic). */
 #define VARLEN_ATTN_TILE_ROWS 128
+#define VARLEN_ATTN_STEP_ROWS 64
 
 /* Status codes (0 = success, negative = error). */
 #define VARLEN_ATTN_OK 0
@@ -54,6 +63,10 @@ extern "C" {
 #define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* bwd only: the workspace still holds the plan that a
                                          preceding varlen_attn_fwd / varlen_attn_plan call
                                          with the same params and cu_seqlens wrote */
+#define VARLEN_ATTN_FLAG_NO_SPLIT 2   /* never cut a chain: every document is then computed
+                                         exactly as if it were alone in the microbatch
+                                         (bit-identical results under repacking), at the
+                                         price of idle compute units on short microbatches */
 
 typedef struct {
   int32_t total_tokens;  /* N   >= 1 */
@@ -65,31 +78,70 @@ typedef struct {
   int32_t flags;         /* VARLEN_ATTN_FLAG_* */
 } varlen_attn_params;
 
-/* Work item of the plan: one tile of one document.  Items are ordered by non-increasing
- * cost (number of tiles at or below it in its document), i.e. longest job first. */
+/* Work unit of the plan: a chunk [step_begin, step_end) of the chain of one tile.  Units are
+ * ordered by non-increasing cost (longest job first); the order among equal costs is not
+ * defined. */
 typedef struct {
-  int32_t row0;      /* first token of the tile */
-  int32_t doc_start; /* cu[b]   */
-  int32_t doc_end;   /* cu[b+1] */
-  int32_t cost;      /* tile index inside the document + 1 */
-} varlen_attn_item;
+  int32_t row0;       /* first token of the tile */
+  int32_t doc_start;  /* cu[b]   */
+  int32_t doc_end;    /* cu[b+1] */
+  int32_t step_begin; /* first step of the chain this unit covers */
+  int32_t step_end;   /* one past its last step */
+  int32_t slot;       /* partial-result slot, or -1 when the unit covers the whole chain and
+                         writes the final output itself */
+  int32_t cost;       /* step_end - step_begin */
+  int32_t reserved;
+} varlen_attn_unit;
+
+/* A tile whose partial results (slots slot0 .. slot0 + n_chunks - 1) must be summed. */
+typedef struct {
+  int32_t row0;
+  int32_t doc_end;
+  int32_t slot0;
+  int32_t n_chunks;
+} varlen_attn_combine_item;
 
 /* Header at the start of the workspace, written by the plan step. */
 typedef struct {
-  int32_t n_items;   /* number of work items that follow */
-  int32_t status;    /* VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS */
-  int64_t pairs;     /* sum_b l_b (l_b + 1) / 2: (query, key) pairs inside the mask */
-  int32_t max_items; /* capacity of the item array: N / TILE_ROWS + B */
-  int32_t reserved[3];
+  int32_t status;          /* VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS */
+  int32_t n_row_units;     /* units of the forward / dQ direction */
+  int32_t n_col_units;     /* units of the dK/dV direction */
+  int32_t n_row_combine;   /* tiles whose row chain was cut */
+  int32_t n_col_combine;   /* tiles whose column chain was cut, or all tiles when Hq > Hkv */
+  int32_t row_chunk_steps; /* longest chunk allowed in a row chain */
+  int32_t col_chunk_steps; /* longest chunk allowed in a column chain */
+  int32_t n_row_slots;
+  int32_t n_col_slots;
+  int32_t sorted;          /* 1: units are in non-increasing cost order (large microbatches);
+                              0: sweep order (every unit is short anyway) */
+  int32_t reserved[4];
+  int64_t pairs;           /* sum_b l_b (l_b + 1) / 2: (query, key) pairs inside the mask */
 } varlen_attn_plan_header;
 
-/* Workspace layout: [plan header][max_items items][fp32 D, Hq * N (backward only)].
- * Bytes the caller must provide (device memory, 16-byte aligned); 0 if params are invalid.
- * Host function, no device work. */
+/* Byte offsets and capacities of the regions of the workspace (host function). */
+typedef struct {
+  size_t row_units_offset;
+  size_t col_units_offset;
+  size_t row_combine_offset;
+  size_t col_combine_offset;
+  size_t dsum_offset;         /* fp32 D = rowsum(dO * O), [Hq, N] */
+  size_t row_partials_offset; /* fp32 partial results of cut row chains */
+  size_t col_partials_offset; /* fp32 partial results of cut / grouped column chains */
+  size_t total_bytes;
+  int32_t max_units;          /* capacity of each unit array */
+  int32_t max_combine;        /* capacity of each combine array */
+  int32_t max_row_slots;
+  int32_t max_col_slots;
+} varlen_attn_workspace_layout;
+
+/* Bytes the caller must provide (device memory, 16-byte aligned); 0 if params are invalid.
+ * The size depends on the params only, never on the contents of cu_seqlens: the plan
+ * lengthens its chunks until the partial results fit.  Host function, no device work. */
 size_t varlen_attn_workspace_bytes(const varlen_attn_params* params);
 
-/* Byte offset of the item array inside the workspace (host function). */
-size_t varlen_attn_workspace_items_offset(const varlen_attn_params* params);
+/* Fills `out`; returns VARLEN_ATTN_OK or VARLEN_ATTN_INVALID_ARG / UNSUPPORTED (host function). */
+int varlen_attn_workspace_regions(const varlen_attn_params* params,
+                                  varlen_attn_workspace_layout* out);
 
 /* Plan step alone (it is also the first step of varlen_attn_fwd and, unless
  * VARLEN_ATTN_FLAG_REUSE_PLAN is set, of varlen_attn_bwd): reads cu_seqlens on the device,

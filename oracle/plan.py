@@ -51,3 +51,25 @@ def causal_tile_pairs(cu, block_q: int, block_k: int) -> int:
             last_row = min(l, (i + 1) * block_q) - 1          # inside the document
             total += last_row // block_k + 1
     return total
+
+
+def row_chain_steps(cu, tile_rows: int, step_rows: int):
+    """Forward / dQ direction.  For every tile (doc, i, row0, rows) the number of key steps
+    of `step_rows` rows, counted from the first token of the document, that hold at least
+    one key some query of the tile may see."""
+    cu = [int(x) for x in cu]
+    out = {}
+    for b, i, r0, rows in row_tiles(cu, tile_rows):
+        last = r0 + rows - 1
+        out[(r0, cu[b], cu[b + 1])] = (last - cu[b]) // step_rows + 1
+    return out
+
+
+def col_chain_steps(cu, tile_rows: int, step_rows: int):
+    """dK / dV direction.  For every tile the number of query steps of `step_rows` rows,
+    counted from the first row of the tile, up to the end of the document."""
+    cu = [int(x) for x in cu]
+    out = {}
+    for b, i, r0, rows in row_tiles(cu, tile_rows):
+        out[(r0, cu[b], cu[b + 1])] = -(-(cu[b + 1] - r0) // step_rows)
+    return out

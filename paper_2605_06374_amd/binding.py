@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libvarlen_attn.so")
 
 TILE_ROWS = 128
+STEP_ROWS = 64
 OK = 0
 INVALID_ARG = -1
 UNSUPPORTED = -2
@@ -22,6 +23,7 @@ WORKSPACE_TOO_SMALL = -3
 LAUNCH_FAILED = -4
 BAD_CU_SEQLENS = -5
 FLAG_REUSE_PLAN = 1
+FLAG_NO_SPLIT = 2
 
 
 class Params(ctypes.Structure):
@@ -32,19 +34,39 @@ class Params(ctypes.Structure):
 
 
 class PlanHeader(ctypes.Structure):
-    _fields_ = [("n_items", ctypes.c_int32), ("status", ctypes.c_int32),
-                ("pairs", ctypes.c_int64), ("max_items", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 3)]
+    _fields_ = [("status", ctypes.c_int32), ("n_row_units", ctypes.c_int32),
+                ("n_col_units", ctypes.c_int32), ("n_row_combine", ctypes.c_int32),
+                ("n_col_combine", ctypes.c_int32), ("row_chunk_steps", ctypes.c_int32),
+                ("col_chunk_steps", ctypes.c_int32), ("n_row_slots", ctypes.c_int32),
+                ("n_col_slots", ctypes.c_int32), ("sorted", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 4),
+                ("pairs", ctypes.c_int64)]
+
+
+class Unit(ctypes.Structure):
+    _fields_ = [("row0", ctypes.c_int32), ("doc_start", ctypes.c_int32),
+                ("doc_end", ctypes.c_int32), ("step_begin", ctypes.c_int32),
+                ("step_end", ctypes.c_int32), ("slot", ctypes.c_int32),
+                ("cost", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class CombineItem(ctypes.Structure):
+    _fields_ = [("row0", ctypes.c_int32), ("doc_end", ctypes.c_int32),
+                ("slot0", ctypes.c_int32), ("n_chunks", ctypes.c_int32)]
+
+
+class WorkspaceLayout(ctypes.Structure):
+    _fields_ = [("row_units_offset", ctypes.c_size_t), ("col_units_offset", ctypes.c_size_t),
+                ("row_combine_offset", ctypes.c_size_t), ("col_combine_offset", ctypes.c_size_t),
+                ("dsum_offset", ctypes.c_size_t), ("row_partials_offset", ctypes.c_size_t),
+                ("col_partials_offset", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t),
+                ("max_units", ctypes.c_int32), ("max_combine", ctypes.c_int32),
+                ("max_row_slots", ctypes.c_int32), ("max_col_slots", ctypes.c_int32)]
 
 
 class KernelTime(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int32),
                 ("total_ms", ctypes.c_float)]
-
-
-class Item(ctypes.Structure):
-    _fields_ = [("row0", ctypes.c_int32), ("doc_start", ctypes.c_int32),
-                ("doc_end", ctypes.c_int32), ("cost", ctypes.c_int32)]
 
 
 _lib = None
@@ -61,8 +83,8 @@ def lib() -> ctypes.CDLL:
         vp, sz, pp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(Params)
         L.varlen_attn_workspace_bytes.restype = sz
         L.varlen_attn_workspace_bytes.argtypes = [pp]
-        L.varlen_attn_workspace_items_offset.restype = sz
-        L.varlen_attn_workspace_items_offset.argtypes = [pp]
+        L.varlen_attn_workspace_regions.restype = ctypes.c_int
+        L.varlen_attn_workspace_regions.argtypes = [pp, ctypes.POINTER(WorkspaceLayout)]
         L.varlen_attn_plan.restype = ctypes.c_int
         L.varlen_attn_plan.argtypes = [pp, vp, vp, sz, vp]
         L.varlen_attn_fwd.restype = ctypes.c_int
@@ -114,8 +136,10 @@ def varlen_attn_workspace_bytes(params: Params) -> int:
     return int(lib().varlen_attn_workspace_bytes(ctypes.byref(params)))
 
 
-def varlen_attn_workspace_items_offset(params: Params) -> int:
-    return int(lib().varlen_attn_workspace_items_offset(ctypes.byref(params)))
+def varlen_attn_workspace_regions(params: Params) -> WorkspaceLayout:
+    out = WorkspaceLayout()
+    check(int(lib().varlen_attn_workspace_regions(ctypes.byref(params), ctypes.byref(out))))
+    return out
 
 
 def varlen_attn_plan(params, cu_seqlens, workspace, workspace_bytes=None, stream=None) -> int:

@@ -16,6 +16,9 @@ FLAGS = [
     "-I" + os.path.join(ROOT, "include"),
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # uniform-address LDS atomics from a few lanes: the optimizer's lane-by-lane reduction
+    # loop costs far more than the atomic it saves
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wno-unused-command-line-argument",
 ]
 

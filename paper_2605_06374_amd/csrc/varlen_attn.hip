@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -35,8 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTile = VARLEN_ATTN_TILE_ROWS;  // rows of a work item (4 waves x 32)
-constexpr int kKvStep = 64;                   // key rows staged per iteration (fwd, dQ)
-constexpr int kQStep = 64;                    // query rows staged per iteration (dK/dV)
+constexpr int kStep = VARLEN_ATTN_STEP_ROWS;  // rows staged per iteration of a chain
 constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -147,112 +147,272 @@ struct TileStager {
 };
 
 // ----------------------------------------------------------------------------------------
-// Plan: cu_seqlens -> validated, cost-ordered tile list (integer work only).
-// One workgroup of 1024 threads.  Items are placed by a counting sort on cost, descending
-// (longest job first); the order among items of equal cost is not defined.
+// Plan: cu_seqlens -> validated work units (integer work only).
+//
+// One workgroup.  For both directions (0: row chains for forward / dQ, 1: column chains for
+// dK / dV) it picks the chunk length, cuts every tile's chain into nearly equal chunks and
+// writes the units.  Chunk length: at least kMinChunkSteps, and long enough that (a) about
+// kTargetUnits (unit, head) pairs exist and (b) the partial-result slots fit the workspace.
+// Small microbatches (every unit is short anyway) are written in sweep order; large ones are
+// placed by a counting sort on cost, descending (longest job first).
+//
+// The kernel runs once per microbatch on a single compute unit with a cold instruction
+// cache, so its latency follows the amount of code it executes: the two directions and the
+// two passes share one copy of the per-tile code (loops deliberately not unrolled).
 // ----------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanBins = 1024;
+constexpr int kMinChunkSteps = 8;
+constexpr int kTargetUnits = 2048;
+constexpr int kNoSplitSteps = 1 << 28;
+constexpr long long kSortAboveSteps = 16384;  // (tile step, head) pairs; below: sweep order
 
-// Visit every (document, tile) pair once: lanes own documents for the first kLaneTiles tiles,
-// then whole waves sweep the remaining tiles of long documents.
-template <typename F>
-__device__ __forceinline__ void for_each_tile(const int32_t* cu, int B, F f) {
-  constexpr int kLaneTiles = 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = kPlanThreads / 64;
-  for (int b0 = wave * 64; b0 < B; b0 += nwaves * 64) {
-    const int b = b0 + lane;
-    int s = 0, e = 0;
-    if (b < B) { s = cu[b]; e = cu[b + 1]; }
-    const int T = (e - s + kTile - 1) / kTile;
-    for (int i = 0; i < kLaneTiles && i < T; ++i) f(s, e, i);
-    unsigned long long longdocs = __ballot(T > kLaneTiles);
-    while (longdocs) {
-      const int src = __ffsll((long long)longdocs) - 1;
-      longdocs &= longdocs - 1;
-      const int ss = __shfl(s, src), ee = __shfl(e, src), TT = __shfl(T, src);
-      for (int i = kLaneTiles + lane; i < TT; i += 64) f(ss, ee, i);
-    }
-  }
-}
+struct PlanArgs {
+  const int32_t* cu;
+  int B, N, Hq, g, shift, no_split;
+  varlen_attn_plan_header* hdr;
+  varlen_attn_unit* units[2];
+  varlen_attn_combine_item* comb[2];
+  int max_units, max_combine, max_slots[2], slots_cap;
+};
 
-__global__ void __launch_bounds__(kPlanThreads) plan_kernel(const int32_t* __restrict__ cu, int B,
-                                                            int N, int shift,
-                                                            varlen_attn_plan_header* hdr,
-                                                            varlen_attn_item* items,
-                                                            int max_items) {
+__global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   __shared__ int bad;
-  __shared__ int hist[kPlanBins];    // tiles per cost bucket, then start offsets (descending)
-  __shared__ int cursor[kPlanBins];
-  __shared__ unsigned long long pairs;
-  const int tid = threadIdx.x;
-  if (tid == 0) { bad = (cu[0] != 0) || (cu[B] != N); pairs = 0; }
-  hist[tid] = 0;
-  cursor[tid] = 0;
-  __syncthreads();
-  unsigned long long my_pairs = 0;
-  int my_bad = 0;
-  for (int b = tid; b < B; b += kPlanThreads) {
-    const long long l = (long long)cu[b + 1] - cu[b];
-    if (l < 0) my_bad = 1;
-    my_pairs += (unsigned long long)(l * (l + 1) / 2);
+  __shared__ int hist[2][kPlanBins];    // units per cost bucket, then start offsets
+  __shared__ int cursor[2][kPlanBins];
+  __shared__ int wsum[kPlanThreads / 64];
+  __shared__ unsigned long long pairs, steps[2];
+  __shared__ int split[2], n_units[2], n_slots[2], n_comb[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* cu = a.cu;
+  if (tid == 0) {
+    bad = (cu[0] != 0) || (cu[a.B] != a.N);
+    pairs = steps[0] = steps[1] = 0;
   }
-  if (my_bad) bad = 1;
+  if (tid < 2) split[tid] = n_units[tid] = n_slots[tid] = n_comb[tid] = 0;
   __syncthreads();
-  if (bad) {
-    if (tid == 0) {
-      hdr->n_items = 0; hdr->status = VARLEN_ATTN_BAD_CU_SEQLENS; hdr->pairs = 0;
-      hdr->max_items = max_items; hdr->reserved[0] = hdr->reserved[1] = hdr->reserved[2] = 0;
+  {
+    unsigned long long my_pairs = 0, my_r = 0, my_c = 0;
+    int my_bad = 0;
+#pragma unroll 1
+    for (int b = tid; b < a.B; b += kPlanThreads) {
+      const long long l = (long long)cu[b + 1] - cu[b];
+      if (l < 0) { my_bad = 1; continue; }
+      my_pairs += (unsigned long long)(l * (l + 1) / 2);
+      const long long T = (l + kTile - 1) / kTile, S = (l + kStep - 1) / kStep;
+      my_r += (unsigned long long)(T * (T - 1) + S);
+      my_c += (unsigned long long)(T * S - T * (T - 1));
     }
+    if (my_bad) bad = 1;
+    if (my_pairs) { atomicAdd(&pairs, my_pairs); atomicAdd(&steps[0], my_r); atomicAdd(&steps[1], my_c); }
+  }
+  __syncthreads();
+  varlen_attn_plan_header* hdr = a.hdr;
+  if (bad) {
+    if (tid < (int)(sizeof(varlen_attn_plan_header) / 4)) reinterpret_cast<int32_t*>(hdr)[tid] = 0;
+    __syncthreads();
+    if (tid == 0) hdr->status = VARLEN_ATTN_BAD_CU_SEQLENS;
     return;
   }
-  if (my_pairs) atomicAdd(&pairs, my_pairs);
-  for_each_tile(cu, B, [&](int, int, int i) { atomicAdd(&hist[i >> shift], 1); });
-  __syncthreads();
-  // start[k] = number of tiles in buckets above k  (exclusive suffix sum, Hillis-Steele)
-  int v = hist[tid];
-  const int own = v;
-  for (int off = 1; off < kPlanBins; off <<= 1) {
-    const int other = (tid + off < kPlanBins) ? hist[tid + off] : 0;
-    __syncthreads();
-    v += other;
-    hist[tid] = v;
-    __syncthreads();
+  const bool sorted = (long long)steps[0] * a.Hq > kSortAboveSteps;
+  int ch[2];
+#pragma unroll
+  for (int d = 0; d < 2; ++d) {
+    ch[d] = kNoSplitSteps;
+    if (!a.no_split) {
+      // 2 * steps / ch bounds the slots of the chains that get cut (each has > ch steps)
+      const long long by_units = (long long)((steps[d] * a.Hq + kTargetUnits - 1) / kTargetUnits);
+      const long long by_slots = (long long)((2 * steps[d] + a.slots_cap - 1) / a.slots_cap);
+      ch[d] = (int)max((long long)kMinChunkSteps, sorted ? by_units : max(by_units, by_slots));
+    }
   }
-  const int total = hist[0];
+  if (sorted) {
+    hist[0][tid] = hist[1][tid] = 0;
+    cursor[0][tid] = cursor[1][tid] = 0;
+  }
   __syncthreads();
-  hist[tid] = v - own;
-  __syncthreads();
-  for_each_tile(cu, B, [&](int s, int e, int i) {
-    const int k = i >> shift;
-    const int pos = hist[k] + atomicAdd(&cursor[k], 1);
-    if (pos < max_items) items[pos] = varlen_attn_item{s + i * kTile, s, e, i + 1};
-  });
+
+  // mode 0: count unit costs (sorted plans only); mode 1: write units.
+  int mode = sorted ? 0 : 1;
+#pragma unroll 1
+  for (;;) {
+    // Every (document, tile) once: lanes take tile 0 of their own document, then whole waves
+    // sweep tiles 1.. of each longer document.  One call site for the per-tile code.
+#pragma unroll 1
+    for (int b0 = wave * 64; b0 < a.B; b0 += (kPlanThreads / 64) * 64) {
+      const int b = b0 + lane;
+      int s = 0, e = 0;
+      if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
+      const int T = (e - s + kTile - 1) / kTile;
+      unsigned long long pending = __ballot(T > 1);
+      int ss = s, ee = e, i = 0, TT = min(T, 1);
+#pragma unroll 1
+      for (;;) {
+#pragma unroll 1
+        while (__any(i < TT)) {
+          if (i < TT) {
+            const int row0 = ss + i * kTile;
+#pragma unroll 1
+            for (int d = 0; d < 2; ++d) {
+              const int n = d == 0 ? (min(row0 + kTile, ee) - 1 - ss) / kStep + 1
+                                   : (ee - row0 + kStep - 1) / kStep;
+              const int nc = (n + ch[d] - 1) / ch[d], base = n / nc, rem = n % nc;
+              if (mode == 0) {
+                atomicAdd(&hist[d][(base - 1) >> a.shift], nc - rem);
+                if (rem) atomicAdd(&hist[d][base >> a.shift], rem);
+                if (nc > 1) atomicAdd(&split[d], nc);
+              } else {
+                int slot0 = -1;
+                if (nc > 1 || (d == 1 && a.g > 1)) {
+                  slot0 = atomicAdd(&n_slots[d], nc);
+                  const int ci = atomicAdd(&n_comb[d], 1);
+                  if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
+                    a.comb[d][ci] = varlen_attn_combine_item{row0, ee, slot0, nc};
+                }
+                int pos0 = sorted ? 0 : atomicAdd(&n_units[d], nc);
+#pragma unroll 1
+                for (int c = 0; c < nc; ++c) {
+                  const int b_ = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
+                  int pos = pos0 + c;
+                  if (sorted) {
+                    const int k = (len - 1) >> a.shift;
+                    pos = hist[d][k] + atomicAdd(&cursor[d][k], 1);
+                  }
+                  if (pos < a.max_units)
+                    a.units[d][pos] = varlen_attn_unit{row0, ss, ee, b_, b_ + len,
+                                                       slot0 < 0 ? -1 : slot0 + c, len, 0};
+                }
+              }
+            }
+          }
+          i += 64;
+        }
+        if (!pending) break;
+        const int src = __ffsll((long long)pending) - 1;
+        pending &= pending - 1;
+        ss = __shfl(s, src); ee = __shfl(e, src); TT = __shfl(T, src);
+        i = 1 + lane;
+      }
+    }
+    __syncthreads();
+    if (mode == 1) break;
+    // sorted plans: lengthen the chunks until the cut chains fit, then turn the histograms
+    // into start offsets (exclusive suffix sums: longest first)
+    const bool fit0 = split[0] <= a.slots_cap, fit1 = split[1] <= a.slots_cap;
+    __syncthreads();
+    if (!(fit0 && fit1)) {
+      if (!fit0) ch[0] *= 2;
+      if (!fit1) ch[1] *= 2;
+      hist[0][tid] = hist[1][tid] = 0;
+      if (tid < 2) split[tid] = 0;
+      __syncthreads();
+      continue;
+    }
+#pragma unroll 1
+    for (int d = 0; d < 2; ++d) {
+      const int own = hist[d][tid];
+      int v = own;
+#pragma unroll 1
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_down(v, off);
+        if (lane + off < 64) v += o;
+      }
+      if (lane == 0) wsum[wave] = v;
+      __syncthreads();
+      int above = 0, total = 0;
+#pragma unroll 1
+      for (int w = 0; w < kPlanThreads / 64; ++w) {
+        const int x = wsum[w];
+        total += x;
+        if (w > wave) above += x;
+      }
+      hist[d][tid] = v - own + above;
+      if (tid == 0) n_units[d] = total;
+      __syncthreads();
+    }
+    mode = 1;
+  }
   if (tid == 0) {
-    hdr->n_items = total < max_items ? total : max_items; hdr->status = VARLEN_ATTN_OK;
-    hdr->pairs = (int64_t)pairs; hdr->max_items = max_items;
-    hdr->reserved[0] = hdr->reserved[1] = hdr->reserved[2] = 0;
+    // the capacities are worst-case bounds; an overflow cannot happen, but never trust it
+    const bool ok = n_units[0] <= a.max_units && n_units[1] <= a.max_units &&
+                    n_comb[0] <= a.max_combine && n_comb[1] <= a.max_combine &&
+                    n_slots[0] <= a.max_slots[0] && n_slots[1] <= a.max_slots[1];
+    hdr->status = VARLEN_ATTN_OK;
+    hdr->n_row_units = ok ? n_units[0] : 0;
+    hdr->n_col_units = ok ? n_units[1] : 0;
+    hdr->n_row_combine = ok ? n_comb[0] : 0;
+    hdr->n_col_combine = ok ? n_comb[1] : 0;
+    hdr->row_chunk_steps = ch[0];
+    hdr->col_chunk_steps = ch[1];
+    hdr->n_row_slots = n_slots[0];
+    hdr->n_col_slots = n_slots[1];
+    hdr->sorted = sorted;
+    for (int i = 0; i < 4; ++i) hdr->reserved[i] = 0;
+    hdr->pairs = (int64_t)pairs;
   }
 }
 
 // ----------------------------------------------------------------------------------------
-// Forward.  One workgroup per (item, q head); wave w owns query rows row0 + 32w .. +31.
+// Partial results of a cut chain are kept in "fragment layout": the accumulator registers
+// exactly as the producing wave holds them, so that every store and load is a contiguous
+// 1 KiB per wave: float index (((wave * DB + db) * 4 + rq) * 64 + lane) * 4 + e  for
+// accumulator register r = 4 rq + e of column block db.  128 * D floats per tensor.
+// ----------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void store_frag(float* base, const f32x16 (&acc)[D / 32], int wave,
+                                           int lane) {
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      f32x4 t = {acc[db][4 * rq], acc[db][4 * rq + 1], acc[db][4 * rq + 2], acc[db][4 * rq + 3]};
+      *reinterpret_cast<f32x4*>(base + ((((size_t)wave * (D / 32) + db) * 4 + rq) * 64 + lane) * 4) = t;
+    }
+}
+template <int D>
+__device__ __forceinline__ f32x4 load_frag4(const float* base, int wave, int lane, int db, int rq) {
+  return *reinterpret_cast<const f32x4*>(base + ((((size_t)wave * (D / 32) + db) * 4 + rq) * 64 + lane) * 4);
+}
+template <int D> constexpr size_t frag_floats() { return (size_t)kTile * D; }
+// forward partial: O fragment, then running max m[4][64] and row sum l[4][64]
+template <int D> constexpr size_t fwd_partial_floats() { return frag_floats<D>() + 2 * kThreads; }
+
+// bf16 store of one accumulator row set: lane owns row `row`, columns 32 db + 8 rq + 4h + e
+template <int D>
+__device__ __forceinline__ void store_rows(__bf16* row_ptr, const f32x16 (&acc)[D / 32], int h,
+                                           float mul) {
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int d0 = 32 * db + 8 * rq + 4 * h;
+      *reinterpret_cast<uint2*>(row_ptr + d0) =
+          pack4(acc[db][4 * rq] * mul, acc[db][4 * rq + 1] * mul, acc[db][4 * rq + 2] * mul,
+                acc[db][4 * rq + 3] * mul);
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// Forward.  One workgroup per (row unit, q head); wave w owns query rows row0 + 32w .. +31.
 // Computes S^T = K Q^T so that a query is a lane column; online softmax in the exp2 domain
-// with a lazily updated running max; O^T += V^T P^T.
+// with a lazily updated running max; O^T += V^T P^T.  A unit that covers its whole chain
+// normalises and stores O and LSE; otherwise it stores the unnormalised accumulator with its
+// running max and row sum for fwd_combine_kernel.
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads, 2)
 fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
            const varlen_attn_plan_header* __restrict__ hdr,
-           const varlen_attn_item* __restrict__ items, __bf16* __restrict__ o,
-           float* __restrict__ lse, int N, int Hq, int Hkv, float scale) {
+           const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ o,
+           float* __restrict__ lse, float* __restrict__ partials, int N, int Hq, int Hkv,
+           float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kKvStep * D * 2;
+  constexpr int kTileBytes = kStep * D * 2;
   __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];  // K0 K1 V0 V1
 
-  const int item_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
-  if (item_idx >= hdr->n_items) return;
-  const varlen_attn_item it = items[item_idx];
+  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  if (unit_idx >= hdr->n_row_units) return;
+  const varlen_attn_unit it = units[unit_idx];
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
@@ -262,8 +422,6 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const bool row_valid = my_row < it.doc_end;
   const bool wave_active = wave_row0 < it.doc_end;
   const int wave_last_row = min(wave_row0 + 31, it.doc_end - 1);
-  const int wg_last_row = min(it.row0 + kTile, it.doc_end) - 1;
-  const int n_steps = (wg_last_row - it.doc_start) / kKvStep + 1;
 
   bf16x8 qf[KK];
 #pragma unroll
@@ -283,22 +441,25 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   for (int i = 0; i < DB; ++i) oacc[i] = f32x16(0.f);
   float m_run = -INFINITY, l_run = 0.f;
 
-  TileStager<D, kKvStep> ks, vs;
-  ks.load(kbase, kv_stride, it.doc_start, it.doc_end, tid);
-  vs.load(vbase, kv_stride, it.doc_start, it.doc_end, tid);
-  ks.store(smem, tid);
-  vs.store(smem + 2 * kTileBytes, tid);
+  TileStager<D, kStep> ks, vs;
+  {
+    const int kv0 = it.doc_start + it.step_begin * kStep;
+    ks.load(kbase, kv_stride, kv0, it.doc_end, tid);
+    vs.load(vbase, kv_stride, kv0, it.doc_end, tid);
+    ks.store(smem, tid);
+    vs.store(smem + 2 * kTileBytes, tid);
+  }
   __syncthreads();
 
-  for (int step = 0; step < n_steps; ++step) {
-    const int cur = step & 1;
-    const int kv0 = it.doc_start + step * kKvStep;
+  for (int step = it.step_begin; step < it.step_end; ++step) {
+    const int cur = (step - it.step_begin) & 1;
+    const int kv0 = it.doc_start + step * kStep;
     const char* kt = smem + cur * kTileBytes;
     const char* vt = smem + (2 + cur) * kTileBytes;
-    const bool more = step + 1 < n_steps;
+    const bool more = step + 1 < it.step_end;
     if (more) {
-      ks.load(kbase, kv_stride, kv0 + kKvStep, it.doc_end, tid);
-      vs.load(vbase, kv_stride, kv0 + kKvStep, it.doc_end, tid);
+      ks.load(kbase, kv_stride, kv0 + kStep, it.doc_end, tid);
+      vs.load(vbase, kv_stride, kv0 + kStep, it.doc_end, tid);
     }
     if (wave_active && kv0 <= wave_last_row) {
       f32x16 s[2];
@@ -311,7 +472,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
           s[blk] = mfma(a, qf[kk], s[blk]);
         }
       }
-      if (kv0 + kKvStep - 1 > wave_row0) {  // tile touches the diagonal for some row
+      if (kv0 + kStep - 1 > wave_row0) {  // tile touches the diagonal for some row
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
@@ -365,22 +526,60 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     __syncthreads();
   }
 
+  if (it.slot >= 0) {
+    // a wave that saw no key in this chunk leaves the neutral element (0, -inf, 0)
+    float* part = partials + ((size_t)it.slot * Hq + head) * fwd_partial_floats<D>();
+    store_frag<D>(part, oacc, wave, lane);
+    part[frag_floats<D>() + tid] = m_run;
+    part[frag_floats<D>() + kThreads + tid] = l_run;
+    return;
+  }
   if (!wave_active) return;
   const float l_tot = half_sum(l_run);
   if (row_valid) {
-    const float inv = 1.0f / l_tot;
-    __bf16* orow = o + ((size_t)my_row * Hq + head) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int d0 = 32 * db + 8 * rq + 4 * h;
-        *reinterpret_cast<uint2*>(orow + d0) =
-            pack4(oacc[db][4 * rq] * inv, oacc[db][4 * rq + 1] * inv, oacc[db][4 * rq + 2] * inv,
-                  oacc[db][4 * rq + 3] * inv);
-      }
+    store_rows<D>(o + ((size_t)my_row * Hq + head) * D, oacc, h, 1.0f / l_tot);
     if (h == 0) lse[(size_t)head * N + my_row] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }
+}
+
+// Sums the chunks of a cut row chain:  O = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.
+// Elementwise over the fragment layout: thread t of an (item, head) owns float4 number t of
+// every partial (so all loads are contiguous), chunks are taken in chain order.
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+fwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
+                   const varlen_attn_combine_item* __restrict__ items,
+                   const float* __restrict__ partials, __bf16* __restrict__ o,
+                   float* __restrict__ lse, int N, int Hq) {
+  constexpr int DB = D / 32;
+  constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
+  const int sub = blockIdx.x % kBlocksPerItem, rest = blockIdx.x / kBlocksPerItem;
+  const int idx = rest / Hq, head = rest % Hq;
+  if (idx >= hdr->n_row_combine) return;
+  const varlen_attn_combine_item it = items[idx];
+  const int t = sub * kThreads + threadIdx.x;  // float4 index inside the fragment
+  const int lane = t & 63, rq = (t >> 6) & 3, db = (t >> 8) % DB, wave = (t >> 8) / DB;
+  const int h = lane >> 5, c = lane & 31;
+  const int my_row = it.row0 + 32 * wave + c;
+  if (my_row >= it.doc_end) return;
+  const size_t pstride = (size_t)Hq * fwd_partial_floats<D>();
+  const float* p0 = partials + ((size_t)it.slot0 * Hq + head) * fwd_partial_floats<D>();
+  const float* st = p0 + frag_floats<D>() + wave * 64;  // m[lane], then l[lane] 256 floats on
+  float m = -INFINITY;
+  for (int ch = 0; ch < it.n_chunks; ++ch) m = __builtin_fmaxf(m, st[ch * pstride + lane]);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int ch = 0; ch < it.n_chunks; ++ch) {
+    const float w = __builtin_amdgcn_exp2f(st[ch * pstride + lane] - m);
+    l += w * (st[ch * pstride + kThreads + c] + st[ch * pstride + kThreads + 32 + c]);
+    const f32x4 x = *reinterpret_cast<const f32x4*>(p0 + ch * pstride + (size_t)t * 4);
+    acc += w * x;
+  }
+  const float inv = 1.0f / l;
+  *reinterpret_cast<uint2*>(o + ((size_t)my_row * Hq + head) * D + 32 * db + 8 * rq + 4 * h) =
+      pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+  if (db == 0 && rq == 0 && h == 0)
+    lse[(size_t)head * N + my_row] = (m + __builtin_amdgcn_logf(l)) * kLn2;
 }
 
 // ----------------------------------------------------------------------------------------
@@ -409,9 +608,8 @@ rowdot_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, floa
 }
 
 // ----------------------------------------------------------------------------------------
-// Backward, dQ.  Same decomposition as the forward: one workgroup per (item, q head), key
-// tiles up to the diagonal.  S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - D),
-// dQ^T += K^T dS^T.
+// Backward, dQ.  Same decomposition as the forward: one workgroup per (row unit, q head).
+// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - D), dQ^T += K^T dS^T.
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads, 2)
@@ -419,15 +617,15 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
               const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
               const float* __restrict__ lse, const float* __restrict__ dsum,
               const varlen_attn_plan_header* __restrict__ hdr,
-              const varlen_attn_item* __restrict__ items, __bf16* __restrict__ dq, int N, int Hq,
-              int Hkv, float scale) {
+              const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dq,
+              float* __restrict__ partials, int N, int Hq, int Hkv, float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kKvStep * D * 2;
+  constexpr int kTileBytes = kStep * D * 2;
   __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];  // K0 K1 V0 V1
 
-  const int item_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
-  if (item_idx >= hdr->n_items) return;
-  const varlen_attn_item it = items[item_idx];
+  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  if (unit_idx >= hdr->n_row_units) return;
+  const varlen_attn_unit it = units[unit_idx];
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
@@ -437,8 +635,6 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const bool row_valid = my_row < it.doc_end;
   const bool wave_active = wave_row0 < it.doc_end;
   const int wave_last_row = min(wave_row0 + 31, it.doc_end - 1);
-  const int wg_last_row = min(it.row0 + kTile, it.doc_end) - 1;
-  const int n_steps = (wg_last_row - it.doc_start) / kKvStep + 1;
 
   bf16x8 qf[KK], dof[KK];
 #pragma unroll
@@ -464,25 +660,28 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 #pragma unroll
   for (int i = 0; i < DB; ++i) acc[i] = f32x16(0.f);
 
-  TileStager<D, kKvStep> ks, vs;
-  ks.load(kbase, kv_stride, it.doc_start, it.doc_end, tid);
-  vs.load(vbase, kv_stride, it.doc_start, it.doc_end, tid);
-  ks.store(smem, tid);
-  vs.store(smem + 2 * kTileBytes, tid);
+  TileStager<D, kStep> ks, vs;
+  {
+    const int kv0 = it.doc_start + it.step_begin * kStep;
+    ks.load(kbase, kv_stride, kv0, it.doc_end, tid);
+    vs.load(vbase, kv_stride, kv0, it.doc_end, tid);
+    ks.store(smem, tid);
+    vs.store(smem + 2 * kTileBytes, tid);
+  }
   __syncthreads();
 
-  for (int step = 0; step < n_steps; ++step) {
-    const int cur = step & 1;
-    const int kv0 = it.doc_start + step * kKvStep;
+  for (int step = it.step_begin; step < it.step_end; ++step) {
+    const int cur = (step - it.step_begin) & 1;
+    const int kv0 = it.doc_start + step * kStep;
     const char* kt = smem + cur * kTileBytes;
     const char* vt = smem + (2 + cur) * kTileBytes;
-    const bool more = step + 1 < n_steps;
+    const bool more = step + 1 < it.step_end;
     if (more) {
-      ks.load(kbase, kv_stride, kv0 + kKvStep, it.doc_end, tid);
-      vs.load(vbase, kv_stride, kv0 + kKvStep, it.doc_end, tid);
+      ks.load(kbase, kv_stride, kv0 + kStep, it.doc_end, tid);
+      vs.load(vbase, kv_stride, kv0 + kStep, it.doc_end, tid);
     }
     if (wave_active && kv0 <= wave_last_row) {
-      const bool diag = kv0 + kKvStep - 1 > wave_row0;
+      const bool diag = kv0 + kStep - 1 > wave_row0;
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk) {
         if (kv0 + 32 * blk > wave_last_row) continue;  // wave-uniform
@@ -524,28 +723,21 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     __syncthreads();
   }
 
-  if (row_valid) {
-    __bf16* row = dq + ((size_t)my_row * Hq + head) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int d0 = 32 * db + 8 * rq + 4 * h;
-        *reinterpret_cast<uint2*>(row + d0) =
-            pack4(acc[db][4 * rq] * scale, acc[db][4 * rq + 1] * scale,
-                  acc[db][4 * rq + 2] * scale, acc[db][4 * rq + 3] * scale);
-      }
+  if (it.slot >= 0) {
+    store_frag<D>(partials + ((size_t)it.slot * Hq + head) * frag_floats<D>(), acc, wave, lane);
+    return;
   }
+  if (row_valid) store_rows<D>(dq + ((size_t)my_row * Hq + head) * D, acc, h, scale);
 }
 
 // ----------------------------------------------------------------------------------------
-// Backward, dK and dV.  One workgroup per (mirrored item, kv head): item (doc, tile i) of a
-// document with T tiles handles key tile T-1-i, whose cost (q tiles at or after it) is i+1,
-// so the plan's longest-first order carries over.  Wave w owns key rows kv_row0 + 32w..+31,
-// keeps their K and V fragments in registers, and sweeps the q heads of the group and the
-// query rows from the diagonal to the document end.
+// Backward, dK and dV.  One workgroup per (column unit, q head): wave w owns key rows
+// row0 + 32w .. +31, keeps their K and V fragments in registers, and sweeps the unit's
+// query steps (from the diagonal towards the document end).
 //   S = Q K^T, dP = dO V^T (query rows in registers r, key on the lane),
 //   dV^T += dO^T P,  dK^T += Q^T dS.
+// With grouped-query attention, or when the chain is cut, the unit stores fp32 partials
+// [dK | dV] that sum_combine_kernel adds up over the chunks and the q heads of the group.
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads, 1)
@@ -553,24 +745,23 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
                const float* __restrict__ lse, const float* __restrict__ dsum,
                const varlen_attn_plan_header* __restrict__ hdr,
-               const varlen_attn_item* __restrict__ items, __bf16* __restrict__ dk,
-               __bf16* __restrict__ dv, int N, int Hq, int Hkv, float scale) {
+               const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dk,
+               __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
+               float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kQStep * D * 2;
-  // Q0 Q1 dO0 dO1 tiles, then lse2[2][kQStep], dsum[2][kQStep]
-  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes + 4 * kQStep * 4];
+  constexpr int kTileBytes = kStep * D * 2;
+  // Q0 Q1 dO0 dO1 tiles, then lse2[2][kStep], dsum[2][kStep]
+  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes + 4 * kStep * 4];
   float* stat = reinterpret_cast<float*>(smem + 4 * kTileBytes);
 
-  const int item_idx = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
-  if (item_idx >= hdr->n_items) return;
-  const varlen_attn_item it = items[item_idx];
-  const int g = Hq / Hkv;
+  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  if (unit_idx >= hdr->n_col_units) return;
+  const varlen_attn_unit it = units[unit_idx];
+  const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
 
-  const int n_tiles = (it.doc_end - it.doc_start + kTile - 1) / kTile;
-  const int kv_row0 = it.doc_start + (n_tiles - it.cost) * kTile;
-  const int wave_kv0 = kv_row0 + 32 * wave;
+  const int wave_kv0 = it.row0 + 32 * wave;
   const int my_kv = wave_kv0 + c;
   const bool kv_valid = my_kv < it.doc_end;
   const bool wave_active = wave_kv0 < it.doc_end;
@@ -592,44 +783,43 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 #pragma unroll
   for (int i = 0; i < DB; ++i) { dkacc[i] = f32x16(0.f); dvacc[i] = f32x16(0.f); }
 
-  const int q_steps = (it.doc_end - kv_row0 + kQStep - 1) / kQStep;  // per head
-  const int n_steps = q_steps * g;
   const size_t q_stride = (size_t)Hq * D;
+  const __bf16* qbase = q + (size_t)head * D;
+  const __bf16* dobase = d_o + (size_t)head * D;
 
-  TileStager<D, kQStep> qs, dos;
+  TileStager<D, kStep> qs, dos;
   float stat_reg = 0.f;
   auto stage_load = [&](int step) {
-    const int head = kvh * g + step / q_steps;
-    const int q0 = kv_row0 + (step % q_steps) * kQStep;
-    qs.load(q + (size_t)head * D, q_stride, q0, it.doc_end, tid);
-    dos.load(d_o + (size_t)head * D, q_stride, q0, it.doc_end, tid);
-    if (tid < 2 * kQStep) {
-      const int t = q0 + (tid % kQStep);
-      if (tid < kQStep) stat_reg = t < it.doc_end ? lse[(size_t)head * N + t] * kLog2e : 1e30f;
+    const int q0 = it.row0 + step * kStep;
+    qs.load(qbase, q_stride, q0, it.doc_end, tid);
+    dos.load(dobase, q_stride, q0, it.doc_end, tid);
+    if (tid < 2 * kStep) {
+      const int t = q0 + (tid % kStep);
+      if (tid < kStep) stat_reg = t < it.doc_end ? lse[(size_t)head * N + t] * kLog2e : 1e30f;
       else stat_reg = t < it.doc_end ? dsum[(size_t)head * N + t] : 0.f;
     }
   };
   auto stage_store = [&](int buf) {
     qs.store(smem + buf * kTileBytes, tid);
     dos.store(smem + (2 + buf) * kTileBytes, tid);
-    if (tid < 2 * kQStep) stat[(tid / kQStep) * 2 * kQStep + buf * kQStep + (tid % kQStep)] = stat_reg;
+    if (tid < 2 * kStep) stat[(tid / kStep) * 2 * kStep + buf * kStep + (tid % kStep)] = stat_reg;
   };
-  stage_load(0);
+  stage_load(it.step_begin);
   stage_store(0);
   __syncthreads();
 
-  for (int step = 0; step < n_steps; ++step) {
-    const int cur = step & 1;
-    const int q0 = kv_row0 + (step % q_steps) * kQStep;
+  for (int step = it.step_begin; step < it.step_end; ++step) {
+    const int cur = (step - it.step_begin) & 1;
+    const int q0 = it.row0 + step * kStep;
     const char* qt = smem + cur * kTileBytes;
     const char* dot = smem + (2 + cur) * kTileBytes;
-    const float* lse_t = stat + cur * kQStep;
-    const float* ds_t = stat + 2 * kQStep + cur * kQStep;
-    const bool more = step + 1 < n_steps;
+    const float* lse_t = stat + cur * kStep;
+    const float* ds_t = stat + 2 * kStep + cur * kStep;
+    const bool more = step + 1 < it.step_end;
     if (more) stage_load(step + 1);
     if (wave_active) {
 #pragma unroll
-      for (int qb = 0; qb < kQStep / 32; ++qb) {
+      for (int qb = 0; qb < kStep / 32; ++qb) {
         const int qb0 = q0 + 32 * qb;
         // wave-uniform: block wholly above the diagonal for this wave, or past the document
         if (qb0 + 31 < wave_kv0 || qb0 >= it.doc_end) continue;
@@ -678,34 +868,62 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     __syncthreads();
   }
 
+  if (it.slot >= 0) {
+    float* part = partials + ((size_t)it.slot * Hq + head) * 2 * frag_floats<D>();
+    store_frag<D>(part, dkacc, wave, lane);
+    store_frag<D>(part + frag_floats<D>(), dvacc, wave, lane);
+    return;
+  }
   if (kv_valid) {
-    __bf16* krow = dk + ((size_t)my_kv * Hkv + kvh) * D;
-    __bf16* vrow = dv + ((size_t)my_kv * Hkv + kvh) * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int d0 = 32 * db + 8 * rq + 4 * h;
-        *reinterpret_cast<uint2*>(krow + d0) =
-            pack4(dkacc[db][4 * rq] * scale, dkacc[db][4 * rq + 1] * scale,
-                  dkacc[db][4 * rq + 2] * scale, dkacc[db][4 * rq + 3] * scale);
-        *reinterpret_cast<uint2*>(vrow + d0) =
-            pack4(dvacc[db][4 * rq], dvacc[db][4 * rq + 1], dvacc[db][4 * rq + 2],
-                  dvacc[db][4 * rq + 3]);
-      }
+    store_rows<D>(dk + ((size_t)my_kv * Hkv + kvh) * D, dkacc, h, scale);
+    store_rows<D>(dv + ((size_t)my_kv * Hkv + kvh) * D, dvacc, h, 1.0f);
   }
 }
 
-// ----------------------------------------------------------------------------------------
-// Host side
-// ----------------------------------------------------------------------------------------
+// Adds up fp32 partial fragments in a fixed order (chunks in chain order, then the q heads of
+// the group) and stores bf16 rows.  NT tensors per partial (dQ: 1; [dK | dV]: 2), G partial
+// heads per output head; tensor 0 is multiplied by `scale0`.  Elementwise: thread t owns
+// float4 number t of the fragment.
+template <int D, int NT>
+__global__ void __launch_bounds__(kThreads)
+sum_combine_kernel(const int* __restrict__ n_items_ptr,
+                   const varlen_attn_combine_item* __restrict__ items,
+                   const float* __restrict__ partials, __bf16* __restrict__ out0,
+                   __bf16* __restrict__ out1, int Hin, int G, float scale0) {
+  constexpr int DB = D / 32;
+  constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
+  const int Hout = Hin / G;
+  const int sub = blockIdx.x % kBlocksPerItem;
+  int rest = blockIdx.x / kBlocksPerItem;
+  const int tensor = rest % NT; rest /= NT;
+  const int idx = rest / Hout, oh = rest % Hout;
+  if (idx >= *n_items_ptr) return;
+  const varlen_attn_combine_item it = items[idx];
+  const int t = sub * kThreads + threadIdx.x;
+  const int lane = t & 63, rq = (t >> 6) & 3, db = (t >> 8) % DB, wave = (t >> 8) / DB;
+  const int h = lane >> 5, c = lane & 31;
+  const int my_row = it.row0 + 32 * wave + c;
+  if (my_row >= it.doc_end) return;
+  const size_t psize = NT * frag_floats<D>();
+  const float* p0 = partials + ((size_t)it.slot0 * Hin + oh * G) * psize + tensor * frag_floats<D>() +
+                    (size_t)t * 4;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int ch = 0; ch < it.n_chunks; ++ch)
+    for (int gh = 0; gh < G; ++gh)
+      acc += *reinterpret_cast<const f32x4*>(p0 + ((size_t)ch * Hin + gh) * psize);
+  const float mul = tensor == 0 ? scale0 : 1.0f;
+  __bf16* out = tensor == 0 ? out0 : out1;
+  *reinterpret_cast<uint2*>(out + ((size_t)my_row * Hout + oh) * D + 32 * db + 8 * rq + 4 * h) =
+      pack4(acc[0] * mul, acc[1] * mul, acc[2] * mul, acc[3] * mul);
+}
 
 // ----------------------------------------------------------------------------------------
 // Optional per-kernel timing (host-side HIP events only; off by default).
 // ----------------------------------------------------------------------------------------
-enum KernelId { kPlan = 0, kFwd, kRowdot, kDkv, kDq, kNumKernels };
-const char* const kKernelNames[kNumKernels] = {"plan_kernel", "fwd_kernel", "rowdot_kernel",
-                                               "bwd_dkv_kernel", "bwd_dq_kernel"};
+enum KernelId { kPlan = 0, kFwd, kFwdCombine, kRowdot, kDkv, kDq, kDkvCombine, kDqCombine, kNumKernels };
+const char* const kKernelNames[kNumKernels] = {
+    "plan_kernel", "fwd_kernel", "fwd_combine_kernel", "rowdot_kernel", "bwd_dkv_kernel",
+    "bwd_dq_kernel", "bwd_dkv_combine_kernel", "bwd_dq_combine_kernel"};
 struct Profiler {
   std::mutex mu;
   bool enabled = false;
@@ -737,12 +955,8 @@ struct ScopedKernelTimer {
   ~ScopedKernelTimer() { if (stop) (void)hipEventRecord(stop, stream); }
 };
 
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-struct Layout {
-  int max_items;
-  size_t items_off, dsum_off, total;
-};
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 bool params_ok(const varlen_attn_params* p) {
   if (!p) return false;
@@ -752,21 +966,37 @@ bool params_ok(const varlen_attn_params* p) {
   return true;
 }
 
-bool layout_of(const varlen_attn_params* p, Layout* L) {
-  if (!params_ok(p)) return false;
-  const long long mi = (long long)p->total_tokens / kTile + p->num_docs;
-  if (mi > 0x7fffffffLL / 64) return false;
-  L->max_items = (int)mi;
-  L->items_off = align_up(sizeof(varlen_attn_plan_header), 256);
-  L->dsum_off = align_up(L->items_off + sizeof(varlen_attn_item) * (size_t)mi, 256);
-  L->total = align_up(L->dsum_off + sizeof(float) * (size_t)p->num_q_heads * p->total_tokens, 256);
+// Capacities depend on the params only.  Slots: enough for kTargetUnits (unit, head) pairs,
+// never more than 8 per tile; with grouped-query attention every column tile takes a slot.
+bool layout_of(const varlen_attn_params* p, varlen_attn_workspace_layout* L, int* slots_cap) {
+  if (!params_ok(p) || (p->head_dim != 64 && p->head_dim != 128)) return false;
+  const long long tiles = (long long)p->total_tokens / kTile + p->num_docs;
+  if (tiles > (1 << 24)) return false;
+  const int Hq = p->num_q_heads, g = Hq / p->num_kv_heads;
+  const long long cap = std::min<long long>((kTargetUnits + Hq - 1) / Hq, 8 * tiles);
+  *slots_cap = (int)cap;
+  L->max_units = (int)(tiles + cap);
+  L->max_combine = (int)tiles;
+  L->max_row_slots = (int)cap;
+  L->max_col_slots = (int)(cap + (g > 1 ? tiles : 0));
+  const size_t frag = (size_t)kTile * p->head_dim * sizeof(float);
+  const size_t fwd_part = frag + 2 * kThreads * sizeof(float);
+  size_t off = align_up(sizeof(varlen_attn_plan_header), 256);
+  L->row_units_offset = off; off = align_up(off + sizeof(varlen_attn_unit) * L->max_units, 256);
+  L->col_units_offset = off; off = align_up(off + sizeof(varlen_attn_unit) * L->max_units, 256);
+  L->row_combine_offset = off; off = align_up(off + sizeof(varlen_attn_combine_item) * L->max_combine, 256);
+  L->col_combine_offset = off; off = align_up(off + sizeof(varlen_attn_combine_item) * L->max_combine, 256);
+  L->dsum_offset = off; off = align_up(off + sizeof(float) * (size_t)Hq * p->total_tokens, 256);
+  L->row_partials_offset = off; off = align_up(off + fwd_part * Hq * L->max_row_slots, 256);
+  L->col_partials_offset = off; off = align_up(off + 2 * frag * Hq * L->max_col_slots, 256);
+  L->total_bytes = off;
   return true;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 int check_common(const varlen_attn_params* p, const void* const* ptrs, int n_ptrs, void* ws,
-                 size_t ws_bytes, Layout* L) {
+                 size_t ws_bytes, varlen_attn_workspace_layout* L, int* slots_cap) {
   if (!params_ok(p)) return VARLEN_ATTN_INVALID_ARG;
   for (int i = 0; i < n_ptrs; ++i)
     if (!ptrs[i]) return VARLEN_ATTN_INVALID_ARG;
@@ -775,28 +1005,68 @@ int check_common(const varlen_attn_params* p, const void* const* ptrs, int n_ptr
   for (int i = 0; i < n_ptrs; ++i)
     if (!aligned16(ptrs[i])) return VARLEN_ATTN_UNSUPPORTED;
   if (!aligned16(ws)) return VARLEN_ATTN_UNSUPPORTED;
-  if (!layout_of(p, L)) return VARLEN_ATTN_UNSUPPORTED;
-  if (ws_bytes < L->total) return VARLEN_ATTN_WORKSPACE_TOO_SMALL;
+  if (!layout_of(p, L, slots_cap)) return VARLEN_ATTN_UNSUPPORTED;
+  if (ws_bytes < L->total_bytes) return VARLEN_ATTN_WORKSPACE_TOO_SMALL;
   return VARLEN_ATTN_OK;
 }
 
-int launch_plan(const varlen_attn_params* p, const int32_t* cu, char* ws, const Layout& L,
-                hipStream_t stream) {
+struct Regions {
+  varlen_attn_plan_header* hdr;
+  varlen_attn_unit *row_units, *col_units;
+  varlen_attn_combine_item *row_comb, *col_comb;
+  float *dsum, *row_part, *col_part;
+};
+Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
+  return Regions{reinterpret_cast<varlen_attn_plan_header*>(ws),
+                 reinterpret_cast<varlen_attn_unit*>(ws + L.row_units_offset),
+                 reinterpret_cast<varlen_attn_unit*>(ws + L.col_units_offset),
+                 reinterpret_cast<varlen_attn_combine_item*>(ws + L.row_combine_offset),
+                 reinterpret_cast<varlen_attn_combine_item*>(ws + L.col_combine_offset),
+                 reinterpret_cast<float*>(ws + L.dsum_offset),
+                 reinterpret_cast<float*>(ws + L.row_partials_offset),
+                 reinterpret_cast<float*>(ws + L.col_partials_offset)};
+}
+
+int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
+                const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream) {
   int shift = 0;
-  const int max_cost = (p->total_tokens + kTile - 1) / kTile;
+  const int max_cost = (p->total_tokens + kStep - 1) / kStep;
   while ((max_cost - 1) >> shift >= kPlanBins) ++shift;
+  PlanArgs a;
+  a.cu = cu; a.B = p->num_docs; a.N = p->total_tokens; a.Hq = p->num_q_heads;
+  a.g = p->num_q_heads / p->num_kv_heads; a.shift = shift;
+  a.no_split = (p->flags & VARLEN_ATTN_FLAG_NO_SPLIT) ? 1 : 0;
+  a.hdr = R.hdr; a.units[0] = R.row_units; a.units[1] = R.col_units;
+  a.comb[0] = R.row_comb; a.comb[1] = R.col_comb;
+  a.max_units = L.max_units; a.max_combine = L.max_combine;
+  a.max_slots[0] = L.max_row_slots; a.max_slots[1] = L.max_col_slots; a.slots_cap = slots_cap;
   ScopedKernelTimer timer(kPlan, stream);
-  plan_kernel<<<1, kPlanThreads, 0, stream>>>(
-      cu, p->num_docs, p->total_tokens, shift, reinterpret_cast<varlen_attn_plan_header*>(ws),
-      reinterpret_cast<varlen_attn_item*>(ws + L.items_off), L.max_items);
+  plan_kernel<<<1, kPlanThreads, 0, stream>>>(a);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
+}
+
+template <int D>
+void launch_fwd(const varlen_attn_params* p, const void* q, const void* k, const void* v, void* o,
+                float* lse, const Regions& R, const varlen_attn_workspace_layout& L,
+                hipStream_t stream) {
+  const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
+  {
+    ScopedKernelTimer timer(kFwd, stream);
+    fwd_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
+        R.row_part, N, Hq, Hkv, p->softmax_scale);
+  }
+  if (!(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT)) {
+    ScopedKernelTimer timer(kFwdCombine, stream);
+    fwd_combine_kernel<D><<<dim3((unsigned)L.max_combine * Hq * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
+        R.hdr, R.row_comb, R.row_part, (__bf16*)o, lse, N, Hq);
+  }
 }
 
 template <int D>
 void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const void* v,
                 const void* o, const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                const varlen_attn_plan_header* hdr, const varlen_attn_item* items, float* dsum,
-                const Layout& L, hipStream_t stream) {
+                const Regions& R, const varlen_attn_workspace_layout& L, hipStream_t stream) {
   const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   const float scale = p->softmax_scale;
   const long long rows = (long long)N * Hq;
@@ -804,19 +1074,30 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   {
     ScopedKernelTimer timer(kRowdot, stream);
     rowdot_kernel<D><<<(unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), kThreads, 0, stream>>>(
-        (const __bf16*)o, (const __bf16*)d_o, dsum, N, Hq);
+        (const __bf16*)o, (const __bf16*)d_o, R.dsum, N, Hq);
   }
   {
     ScopedKernelTimer timer(kDkv, stream);
-    bwd_dkv_kernel<D><<<dim3((unsigned)L.max_items * Hkv), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dk, (__bf16*)dv, N, Hq, Hkv, scale);
+    bwd_dkv_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
+        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale);
   }
   {
     ScopedKernelTimer timer(kDq, stream);
-    bwd_dq_kernel<D><<<dim3((unsigned)L.max_items * Hq), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, dsum, hdr,
-        items, (__bf16*)dq, N, Hq, Hkv, scale);
+    bwd_dq_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
+        R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale);
+  }
+  const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
+  if (split || Hq != Hkv) {
+    ScopedKernelTimer timer(kDkvCombine, stream);
+    sum_combine_kernel<D, 2><<<dim3((unsigned)L.max_combine * Hkv * 2 * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
+        &R.hdr->n_col_combine, R.col_comb, R.col_part, (__bf16*)dk, (__bf16*)dv, Hq, Hq / Hkv, scale);
+  }
+  if (split) {
+    ScopedKernelTimer timer(kDqCombine, stream);
+    sum_combine_kernel<D, 1><<<dim3((unsigned)L.max_combine * Hq * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
+        &R.hdr->n_row_combine, R.row_comb, R.row_part, (__bf16*)dq, nullptr, Hq, 1, scale);
   }
 }
 
@@ -825,52 +1106,45 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
 extern "C" {
 
 size_t varlen_attn_workspace_bytes(const varlen_attn_params* params) {
-  Layout L;
-  if (!params_ok(params) || (params->head_dim != 64 && params->head_dim != 128)) return 0;
-  if (!layout_of(params, &L)) return 0;
-  return L.total;
+  varlen_attn_workspace_layout L;
+  int cap;
+  if (!layout_of(params, &L, &cap)) return 0;
+  return L.total_bytes;
 }
 
-size_t varlen_attn_workspace_items_offset(const varlen_attn_params* params) {
-  Layout L;
-  if (!layout_of(params, &L)) return 0;
-  return L.items_off;
+int varlen_attn_workspace_regions(const varlen_attn_params* params,
+                                  varlen_attn_workspace_layout* out) {
+  if (!out || !params_ok(params)) return VARLEN_ATTN_INVALID_ARG;
+  int cap;
+  if (!layout_of(params, out, &cap)) return VARLEN_ATTN_UNSUPPORTED;
+  return VARLEN_ATTN_OK;
 }
 
 int varlen_attn_plan(const varlen_attn_params* params, const int32_t* cu_seqlens, void* workspace,
                      size_t workspace_bytes, void* hip_stream) {
-  Layout L;
+  varlen_attn_workspace_layout L;
+  int cap;
   const void* ptrs[] = {cu_seqlens};
-  const int rc = check_common(params, ptrs, 1, workspace, workspace_bytes, &L);
+  const int rc = check_common(params, ptrs, 1, workspace, workspace_bytes, &L, &cap);
   if (rc != VARLEN_ATTN_OK) return rc;
-  return launch_plan(params, cu_seqlens, static_cast<char*>(workspace), L,
+  return launch_plan(params, cu_seqlens, regions_of(static_cast<char*>(workspace), L), L, cap,
                      static_cast<hipStream_t>(hip_stream));
 }
 
 int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void* k, const void* v,
                     const int32_t* cu_seqlens, void* o, float* lse, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
-  Layout L;
+  varlen_attn_workspace_layout L;
+  int cap;
   const void* ptrs[] = {q, k, v, cu_seqlens, o, lse};
-  int rc = check_common(params, ptrs, 6, workspace, workspace_bytes, &L);
+  int rc = check_common(params, ptrs, 6, workspace, workspace_bytes, &L, &cap);
   if (rc != VARLEN_ATTN_OK) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  char* ws = static_cast<char*>(workspace);
-  rc = launch_plan(params, cu_seqlens, ws, L, stream);
+  const Regions R = regions_of(static_cast<char*>(workspace), L);
+  rc = launch_plan(params, cu_seqlens, R, L, cap, stream);
   if (rc != VARLEN_ATTN_OK) return rc;
-  const auto* hdr = reinterpret_cast<const varlen_attn_plan_header*>(ws);
-  const auto* items = reinterpret_cast<const varlen_attn_item*>(ws + L.items_off);
-  const int N = params->total_tokens, Hq = params->num_q_heads, Hkv = params->num_kv_heads;
-  const dim3 grid((unsigned)L.max_items * Hq);
-  ScopedKernelTimer timer(kFwd, stream);
-  if (params->head_dim == 128)
-    fwd_kernel<128><<<grid, kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, hdr, items, (__bf16*)o, lse, N, Hq,
-        Hkv, params->softmax_scale);
-  else
-    fwd_kernel<64><<<grid, kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, hdr, items, (__bf16*)o, lse, N, Hq,
-        Hkv, params->softmax_scale);
+  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream);
+  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
@@ -878,23 +1152,19 @@ int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void*
                     const void* o, const float* lse, const void* d_o, const int32_t* cu_seqlens,
                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                     void* hip_stream) {
-  Layout L;
+  varlen_attn_workspace_layout L;
+  int cap;
   const void* ptrs[] = {q, k, v, o, lse, d_o, cu_seqlens, dq, dk, dv};
-  int rc = check_common(params, ptrs, 10, workspace, workspace_bytes, &L);
+  int rc = check_common(params, ptrs, 10, workspace, workspace_bytes, &L, &cap);
   if (rc != VARLEN_ATTN_OK) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  char* ws = static_cast<char*>(workspace);
+  const Regions R = regions_of(static_cast<char*>(workspace), L);
   if (!(params->flags & VARLEN_ATTN_FLAG_REUSE_PLAN)) {
-    rc = launch_plan(params, cu_seqlens, ws, L, stream);
+    rc = launch_plan(params, cu_seqlens, R, L, cap, stream);
     if (rc != VARLEN_ATTN_OK) return rc;
   }
-  const auto* hdr = reinterpret_cast<const varlen_attn_plan_header*>(ws);
-  const auto* items = reinterpret_cast<const varlen_attn_item*>(ws + L.items_off);
-  float* dsum = reinterpret_cast<float*>(ws + L.dsum_off);
-  if (params->head_dim == 128)
-    launch_bwd<128>(params, q, k, v, o, lse, d_o, dq, dk, dv, hdr, items, dsum, L, stream);
-  else
-    launch_bwd<64>(params, q, k, v, o, lse, d_o, dq, dk, dv, hdr, items, dsum, L, stream);
+  if (params->head_dim == 128) launch_bwd<128>(params, q, k, v, o, lse, d_o, dq, dk, dv, R, L, stream);
+  else launch_bwd<64>(params, q, k, v, o, lse, d_o, dq, dk, dv, R, L, stream);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 

@@ -68,14 +68,25 @@ class DeviceProblem:
                                               stream=stream))
 
     def read_plan(self):
-        """Header and item list as Python objects (synchronises)."""
-        torch.cuda.synchronize(self.device)
-        raw = self.workspace.cpu().numpy()
+        """Header, unit lists and combine lists as numpy arrays (synchronises).
+        Units: columns row0, doc_start, doc_end, step_begin, step_end, slot, cost, reserved;
+        combine items: row0, doc_end, slot0, n_chunks."""
         import ctypes
+        torch.cuda.synchronize(self.device)
+        L = binding.varlen_attn_workspace_regions(self.params)
+        nbytes = max(L.col_combine_offset + 16 * L.max_combine, 64)
+        raw = self.workspace[:nbytes].cpu().numpy()
         hdr = binding.PlanHeader.from_buffer_copy(raw[:ctypes.sizeof(binding.PlanHeader)].tobytes())
-        off = binding.varlen_attn_workspace_items_offset(self.params)
-        items = np.frombuffer(raw[off:off + 16 * hdr.n_items].tobytes(), dtype=np.int32).reshape(-1, 4)
-        return hdr, items
+
+        def table(off, n, width):
+            return np.frombuffer(raw[off:off + 4 * width * n].tobytes(), dtype=np.int32).reshape(-1, width)
+
+        return {"header": hdr,
+                "row_units": table(L.row_units_offset, hdr.n_row_units, 8),
+                "col_units": table(L.col_units_offset, hdr.n_col_units, 8),
+                "row_combine": table(L.row_combine_offset, hdr.n_row_combine, 4),
+                "col_combine": table(L.col_combine_offset, hdr.n_col_combine, 4),
+                "layout": L}
 
     def results(self):
         torch.cuda.synchronize(self.device)

@@ -28,17 +28,30 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(B.Params) == 28
-    assert ctypes.sizeof(B.PlanHeader) == 32
-    assert ctypes.sizeof(B.Item) == 16
+    assert ctypes.sizeof(B.PlanHeader) == 64
+    assert ctypes.sizeof(B.Unit) == 32
+    assert ctypes.sizeof(B.CombineItem) == 16
 
 
 def test_workspace_bytes():
     p = B.make_params(8192, 9, 4, 4, 128, 0.0884)
     n = B.varlen_attn_workspace_bytes(p)
-    items_off = B.varlen_attn_workspace_items_offset(p)
-    assert items_off >= 32 and items_off % 16 == 0
-    max_items = 8192 // 128 + 9
-    assert n >= items_off + 16 * max_items + 4 * 4 * 8192 and n % 256 == 0
+    L = B.varlen_attn_workspace_regions(p)
+    tiles = 8192 // 128 + 9
+    assert L.total_bytes == n and n % 256 == 0
+    assert L.max_combine == tiles and L.max_units >= tiles + L.max_row_slots
+    assert L.row_units_offset >= 64
+    offs = [L.row_units_offset, L.col_units_offset, L.row_combine_offset, L.col_combine_offset,
+            L.dsum_offset, L.row_partials_offset, L.col_partials_offset, L.total_bytes]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert L.col_units_offset - L.row_units_offset >= 32 * L.max_units
+    assert L.row_partials_offset - L.dsum_offset >= 4 * 4 * 8192
+    assert L.col_partials_offset - L.row_partials_offset >= (128 * 128 + 512) * 4 * 4 * L.max_row_slots
+    assert L.total_bytes - L.col_partials_offset >= 2 * 128 * 128 * 4 * 4 * L.max_col_slots
+    # grouped-query attention: every column tile needs a partial slot
+    pg = B.make_params(16384, 7, 8, 1, 128, 0.0884)
+    Lg = B.varlen_attn_workspace_regions(pg)
+    assert Lg.max_col_slots >= Lg.max_row_slots + 16384 // 128 + 7
     for bad in (B.make_params(0, 1, 1, 1, 64, 1.0), B.make_params(8, 0, 1, 1, 64, 1.0),
                 B.make_params(8, 1, 3, 2, 64, 1.0), B.make_params(8, 1, 1, 1, 96, 1.0),
                 B.make_params(8, 1, 1, 1, 64, 0.0), B.make_params(8, 1, 1, 1, 64, float("nan")),
