@@ -20,6 +20,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <mutex>
 #include <vector>
 
@@ -145,6 +146,137 @@ struct TileStager {
     }
   }
 };
+
+// ----------------------------------------------------------------------------------------
+// Global -> LDS staging without registers (global_load_lds_dwordx4): the 64 lanes of a wave
+// write 1 KiB contiguous in LDS starting at the wave-uniform address in M0, each lane taking
+// its 16 bytes from its own global address.  A stage holds kSub = 32 rows of a [rows][D] tile;
+// the XOR swizzle is applied on the global side (lane of physical chunk pc in row r fetches
+// logical chunk pc ^ swz(r)).  Rows past `row_last` are clamped to it: they are finite
+// duplicates that the causal mask (or a zero P) removes, never garbage.
+//
+// The loads are invisible to the compiler's wait-count bookkeeping (inline asm), which is
+// the point: a compiler-inserted wait would be vmcnt(0) before every LDS read.  The kernels
+// wait explicitly with wait_vm<N>() and publish with a barrier.  Extra outstanding loads can
+// only make compiler-inserted vmcnt waits longer, never too short (in-order completion).
+// ----------------------------------------------------------------------------------------
+constexpr int kSub = 32;  // rows per pipeline stage
+
+// base: wave-uniform 64-bit address; voff: this lane's unsigned byte offset from it
+__device__ __forceinline__ void dma16(unsigned long long base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(base), "s"(lds_addr)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt immediate");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// vmcnt(0) as an instruction the compiler's wait-count pass can see (expcnt, lgkmcnt untouched)
+__device__ __forceinline__ void wait_all_vm_visible() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ __forceinline__ unsigned long long uniform64(const void* p) {
+  const unsigned long long v = (unsigned long long)(size_t)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// Loads 32-row stages of a [rows][D] bf16 tile whose rows are `stride_bytes` apart.  The
+// per-lane part of the address is a 32-bit offset fixed at init; the stage's first row goes
+// into the wave-uniform base, so a stage costs no vector arithmetic unless it runs past
+// `row_last` (then rows are clamped lane by lane).
+template <int D>
+struct StageLoader {
+  static constexpr int kRowsPerInstr = 1024 / (D * 2);      // 4 (D=128), 8 (D=64)
+  static constexpr int kInstr = kSub / kRowsPerInstr;       // 8, 4
+  static constexpr int kPerWave = kInstr / 4;               // 2, 1  (4 waves share a stage)
+  int row_in_stage[kPerWave];
+  unsigned col_bytes[kPerWave];
+  unsigned voff[kPerWave];
+  unsigned stride_bytes;
+  __device__ __forceinline__ void init(int wave, int lane, unsigned stride_bytes_) {
+    stride_bytes = stride_bytes_;
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const int j = wave + 4 * i;
+      const int r = kRowsPerInstr * j + lane / (D / 8), pc = lane % (D / 8);
+      row_in_stage[i] = r;
+      col_bytes[i] = (unsigned)((pc ^ swz<D>(r)) * 16);
+      voff[i] = (unsigned)r * stride_bytes + col_bytes[i];
+    }
+  }
+  // tile rows [row0, row0 + 32) of `base` -> LDS at `lds`; rows above row_last are clamped
+  __device__ __forceinline__ void issue(const __bf16* base, int row0, int row_last, unsigned lds,
+                                        int wave) const {
+    if (row0 + kSub - 1 <= row_last) {
+      const unsigned long long b = uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
+#pragma unroll
+      for (int i = 0; i < kPerWave; ++i)
+        dma16(b, voff[i], __builtin_amdgcn_readfirstlane(lds + (wave + 4 * i) * 1024));
+    } else {
+      const unsigned long long b = uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
+#pragma unroll
+      for (int i = 0; i < kPerWave; ++i) {
+        const int r = min(row_in_stage[i], row_last - row0);   // row_last >= row0 always
+        dma16(b, (unsigned)r * stride_bytes + col_bytes[i],
+              __builtin_amdgcn_readfirstlane(lds + (wave + 4 * i) * 1024));
+      }
+    }
+  }
+};
+
+// per-lane byte offsets (inside a stage) of the two kinds of fragment reads
+template <int D>
+struct FragOffsets {
+  int row_frag[D / 16];     // A/B row fragment of row c, k slice kk: chunk 2kk + h
+  int trans[D / 32][2];     // transposed fragment, column block db, rows 4h + i/4 (+8)
+  __device__ __forceinline__ void init(int lane) {
+    const int h = lane >> 5, c = lane & 31, i = lane & 15, b16 = (lane >> 4) & 1;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) row_frag[kk] = chunk_off<D>(c, 2 * kk + h);
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int second = 0; second < 2; ++second) {
+        const int row = 4 * h + (i >> 2) + 8 * second;
+        const int chunk = 4 * db + 2 * b16 + ((i & 3) >> 1);
+        trans[db][second] = chunk_off<D>(row, chunk) + (i & 1) * 8;
+      }
+  }
+};
+// transposed A operand for rows 16 cc + {4h.., 8 + 4h..} of a stage, column block db
+template <int D>
+__device__ __forceinline__ bf16x8 read_trans(const char* stage, const FragOffsets<D>& fo, int cc,
+                                             int db) {
+  bf16x4 lo = lds_read_tr(stage + fo.trans[db][0] + cc * 16 * D * 2);
+  bf16x4 hi = lds_read_tr(stage + fo.trans[db][1] + cc * 16 * D * 2);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Decode the id so
+// that all units of one head land on the same XCDs and share its K/V (or Q/dO) lines in L2.
+__device__ __forceinline__ void decode_block(int bid, int Hq, int& unit, int& head) {
+  constexpr int kXcds = 8;
+  const int xcd = bid % kXcds, local = bid / kXcds;
+  if (kXcds % Hq == 0) {
+    const int per = kXcds / Hq;          // XCDs per head
+    head = xcd % Hq;
+    unit = local * per + xcd / Hq;
+  } else if (Hq % kXcds == 0) {
+    const int per = Hq / kXcds;          // heads per XCD
+    head = xcd + kXcds * (local % per);
+    unit = local / per;
+  } else {
+    unit = bid / Hq;
+    head = bid % Hq;
+  }
+}
+inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)units * Hq + 7) / 8 * 8); }
 
 // ----------------------------------------------------------------------------------------
 // Plan: cu_seqlens -> validated work units (integer work only).
@@ -407,10 +539,13 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
            float* __restrict__ lse, float* __restrict__ partials, int N, int Hq, int Hkv,
            float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kStep * D * 2;
-  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];  // K0 K1 V0 V1
+  constexpr int NS = 4;                              // pipeline stages of 32 keys
+  constexpr int kStageBytes = kSub * D * 2;
+  constexpr int LPS = 2 * StageLoader<D>::kPerWave;  // DMA loads per thread per stage (K and V)
+  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes];  // K stages, V stages
 
-  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  int unit_idx, head;
+  decode_block(blockIdx.x, Hq, unit_idx, head);
   if (unit_idx >= hdr->n_row_units) return;
   const varlen_attn_unit it = units[unit_idx];
   const int kvh = head / (Hq / Hkv);
@@ -422,6 +557,25 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const bool row_valid = my_row < it.doc_end;
   const bool wave_active = wave_row0 < it.doc_end;
   const int wave_last_row = min(wave_row0 + 31, it.doc_end - 1);
+  const int wg_last_row = min(it.row0 + kTile, it.doc_end) - 1;
+  const int kv_begin = it.doc_start + it.step_begin * kStep;
+  const int kv_end = min(it.doc_start + it.step_end * kStep, wg_last_row + 1);
+  const int n_sub = (kv_end - kv_begin + kSub - 1) / kSub;
+
+  const __bf16* kbase = k + (size_t)kvh * D;
+  const __bf16* vbase = v + (size_t)kvh * D;
+  const size_t kv_stride = (size_t)Hkv * D;
+  const unsigned lds_k = lds_addr_of(smem), lds_v = lds_k + NS * kStageBytes;
+
+  StageLoader<D> loader;
+  loader.init(wave, lane, (unsigned)(kv_stride * 2));
+  auto issue = [&](int sub, int stage) {
+    const int row0 = kv_begin + kSub * min(sub, n_sub - 1);
+    loader.issue(kbase, row0, it.doc_end - 1, lds_k + stage * kStageBytes, wave);
+    loader.issue(vbase, row0, it.doc_end - 1, lds_v + stage * kStageBytes, wave);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st, st);
 
   bf16x8 qf[KK];
 #pragma unroll
@@ -431,100 +585,81 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
       t = *reinterpret_cast<const uint4*>(q + ((size_t)my_row * Hq + head) * D + 16 * kk + 8 * h);
     qf[kk] = __builtin_bit_cast(bf16x8, t);
   }
-
-  const __bf16* kbase = k + (size_t)kvh * D;
-  const __bf16* vbase = v + (size_t)kvh * D;
-  const size_t kv_stride = (size_t)Hkv * D;
+  FragOffsets<D> fo;
+  fo.init(lane);
+  // Let the compiler see its own loads complete here, once; otherwise it keeps a vmcnt(0)
+  // for them inside the loop, which would also wait for every prefetch in flight.
+  wait_all_vm_visible();
 
   f32x16 oacc[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i) oacc[i] = f32x16(0.f);
   float m_run = -INFINITY, l_run = 0.f;
 
-  TileStager<D, kStep> ks, vs;
-  {
-    const int kv0 = it.doc_start + it.step_begin * kStep;
-    ks.load(kbase, kv_stride, kv0, it.doc_end, tid);
-    vs.load(vbase, kv_stride, kv0, it.doc_end, tid);
-    ks.store(smem, tid);
-    vs.store(smem + 2 * kTileBytes, tid);
-  }
-  __syncthreads();
-
-  for (int step = it.step_begin; step < it.step_end; ++step) {
-    const int cur = (step - it.step_begin) & 1;
-    const int kv0 = it.doc_start + step * kStep;
-    const char* kt = smem + cur * kTileBytes;
-    const char* vt = smem + (2 + cur) * kTileBytes;
-    const bool more = step + 1 < it.step_end;
-    if (more) {
-      ks.load(kbase, kv_stride, kv0 + kStep, it.doc_end, tid);
-      vs.load(vbase, kv_stride, kv0 + kStep, it.doc_end, tid);
+  // one sub-step: 32 keys against this wave's 32 queries, stage index known at compile time
+  auto compute = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    const int kv0 = kv_begin + kSub * sub;
+    if (!(wave_active && kv0 <= wave_last_row)) return;
+    const char* kt = smem + ST * kStageBytes;
+    const char* vt = smem + (NS + ST) * kStageBytes;
+    f32x16 s = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
+    if (kv0 + kSub - 1 > wave_row0) {  // touches the diagonal for some row
+      const int t = my_row - kv0 - 4 * h;  // key offset 8 (r / 4) + r % 4 is allowed iff <= t
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (8 * (r / 4) + (r % 4) > t) s[r] = -INFINITY;
     }
-    if (wave_active && kv0 <= wave_last_row) {
-      f32x16 s[2];
+    float mx = s[0];
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk) {
-        s[blk] = f32x16(0.f);
+    for (int r = 1; r < 16; ++r) mx = __builtin_fmaxf(mx, s[r]);
+    mx = half_max(mx);
+    const float m_new = __builtin_fmaxf(m_run, mx * cs);
+    if (__any(m_new > m_run + kRescaleTau)) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          bf16x8 a = lds_read_frag(kt, chunk_off<D>(32 * blk + c, 2 * kk + h));
-          s[blk] = mfma(a, qf[kk], s[blk]);
-        }
-      }
-      if (kv0 + kStep - 1 > wave_row0) {  // tile touches the diagonal for some row
+      for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = kv0 + 32 * blk + 8 * (r / 4) + 4 * h + (r % 4);
-            if (j > my_row) s[blk][r] = -INFINITY;
-          }
-      }
-      float mx = s[0][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = __builtin_fmaxf(mx, s[0][r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = __builtin_fmaxf(mx, s[1][r]);
-      mx = half_max(mx);
-      const float m_new = __builtin_fmaxf(m_run, mx * cs);
-      if (__any(m_new > m_run + kRescaleTau)) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
-      }
-      float psum = 0.f;
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[blk][r], cs, -m_run));
-          s[blk][r] = p;
-          psum += p;
-        }
-      l_run += psum;
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 pb = pack8(s[blk], 8 * cc);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 a = lds_read_trans_frag<D>(vt, 32 * blk + 16 * cc, db, lane);
-            oacc[db] = mfma(a, pb, oacc[db]);
-          }
-        }
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
     }
-    if (more) {
-      ks.store(smem + (cur ^ 1) * kTileBytes, tid);
-      vs.store(smem + (2 + (cur ^ 1)) * kTileBytes, tid);
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -m_run));
+      s[r] = p;
+      psum += p;
     }
+    l_run += psum;
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const bf16x8 pb = pack8(s, 8 * cc);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) oacc[db] = mfma(read_trans<D>(vt, fo, cc, db), pb, oacc[db]);
+    }
+  };
+  // iteration `sub`: its stage has landed once at most NS-2 newer stages are in flight; the
+  // barrier also tells that every wave is done with the stage about to be refilled
+  auto body = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    wait_vm<(NS - 2) * LPS>();
     __syncthreads();
+    issue(sub + NS - 1, (ST + NS - 1) % NS);
+    compute(sub, stage_c);
+  };
+  for (int sub = 0; sub < n_sub; sub += NS) {
+    body(sub, std::integral_constant<int, 0>{});
+    if (sub + 1 >= n_sub) break;
+    body(sub + 1, std::integral_constant<int, 1>{});
+    if (sub + 2 >= n_sub) break;
+    body(sub + 2, std::integral_constant<int, 2>{});
+    if (sub + 3 >= n_sub) break;
+    body(sub + 3, std::integral_constant<int, 3>{});
   }
+  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
 
   if (it.slot >= 0) {
     // a wave that saw no key in this chunk leaves the neutral element (0, -inf, 0)
@@ -620,10 +755,13 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
               const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dq,
               float* __restrict__ partials, int N, int Hq, int Hkv, float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kStep * D * 2;
-  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];  // K0 K1 V0 V1
+  constexpr int NS = 4;
+  constexpr int kStageBytes = kSub * D * 2;
+  constexpr int LPS = 2 * StageLoader<D>::kPerWave;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes];  // K stages, V stages
 
-  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  int unit_idx, head;
+  decode_block(blockIdx.x, Hq, unit_idx, head);
   if (unit_idx >= hdr->n_row_units) return;
   const varlen_attn_unit it = units[unit_idx];
   const int kvh = head / (Hq / Hkv);
@@ -635,6 +773,24 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const bool row_valid = my_row < it.doc_end;
   const bool wave_active = wave_row0 < it.doc_end;
   const int wave_last_row = min(wave_row0 + 31, it.doc_end - 1);
+  const int wg_last_row = min(it.row0 + kTile, it.doc_end) - 1;
+  const int kv_begin = it.doc_start + it.step_begin * kStep;
+  const int kv_end = min(it.doc_start + it.step_end * kStep, wg_last_row + 1);
+  const int n_sub = (kv_end - kv_begin + kSub - 1) / kSub;
+
+  const __bf16* kbase = k + (size_t)kvh * D;
+  const __bf16* vbase = v + (size_t)kvh * D;
+  const unsigned lds_k = lds_addr_of(smem), lds_v = lds_k + NS * kStageBytes;
+
+  StageLoader<D> loader;
+  loader.init(wave, lane, (unsigned)((size_t)Hkv * D * 2));
+  auto issue = [&](int sub, int stage) {
+    const int row0 = kv_begin + kSub * min(sub, n_sub - 1);
+    loader.issue(kbase, row0, it.doc_end - 1, lds_k + stage * kStageBytes, wave);
+    loader.issue(vbase, row0, it.doc_end - 1, lds_v + stage * kStageBytes, wave);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st, st);
 
   bf16x8 qf[KK], dof[KK];
 #pragma unroll
@@ -651,77 +807,58 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // rows past the document end get LSE = +huge so that their P is exactly 0
   const float lse2 = row_valid ? lse[(size_t)head * N + my_row] * kLog2e : 1e30f;
   const float dsum_row = row_valid ? dsum[(size_t)head * N + my_row] : 0.f;
-
-  const __bf16* kbase = k + (size_t)kvh * D;
-  const __bf16* vbase = v + (size_t)kvh * D;
-  const size_t kv_stride = (size_t)Hkv * D;
+  FragOffsets<D> fo;
+  fo.init(lane);
+  wait_all_vm_visible();
 
   f32x16 acc[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i) acc[i] = f32x16(0.f);
 
-  TileStager<D, kStep> ks, vs;
-  {
-    const int kv0 = it.doc_start + it.step_begin * kStep;
-    ks.load(kbase, kv_stride, kv0, it.doc_end, tid);
-    vs.load(vbase, kv_stride, kv0, it.doc_end, tid);
-    ks.store(smem, tid);
-    vs.store(smem + 2 * kTileBytes, tid);
-  }
-  __syncthreads();
-
-  for (int step = it.step_begin; step < it.step_end; ++step) {
-    const int cur = (step - it.step_begin) & 1;
-    const int kv0 = it.doc_start + step * kStep;
-    const char* kt = smem + cur * kTileBytes;
-    const char* vt = smem + (2 + cur) * kTileBytes;
-    const bool more = step + 1 < it.step_end;
-    if (more) {
-      ks.load(kbase, kv_stride, kv0 + kStep, it.doc_end, tid);
-      vs.load(vbase, kv_stride, kv0 + kStep, it.doc_end, tid);
+  auto compute = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    const int kv0 = kv_begin + kSub * sub;
+    if (!(wave_active && kv0 <= wave_last_row)) return;
+    const char* kt = smem + ST * kStageBytes;
+    const char* vt = smem + (NS + ST) * kStageBytes;
+    f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
+      dp = mfma(lds_read_frag(vt, fo.row_frag[kk]), dof[kk], dp);
     }
-    if (wave_active && kv0 <= wave_last_row) {
-      const bool diag = kv0 + kStep - 1 > wave_row0;
+    const bool diag = kv0 + kSub - 1 > wave_row0;
+    const int t = my_row - kv0 - 4 * h;
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk) {
-        if (kv0 + 32 * blk > wave_last_row) continue;  // wave-uniform
-        f32x16 s = f32x16(0.f), dp = f32x16(0.f);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          bf16x8 a = lds_read_frag(kt, chunk_off<D>(32 * blk + c, 2 * kk + h));
-          s = mfma(a, qf[kk], s);
-        }
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          bf16x8 a = lds_read_frag(vt, chunk_off<D>(32 * blk + c, 2 * kk + h));
-          dp = mfma(a, dof[kk], dp);
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
-          if (diag) {
-            const int j = kv0 + 32 * blk + 8 * (r / 4) + 4 * h + (r % 4);
-            if (j > my_row) p = 0.f;
-          }
-          s[r] = p * (dp[r] - dsum_row);
-        }
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 dsb = pack8(s, 8 * cc);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 a = lds_read_trans_frag<D>(kt, 32 * blk + 16 * cc, db, lane);
-            acc[db] = mfma(a, dsb, acc[db]);
-          }
-        }
-      }
+    for (int r = 0; r < 16; ++r) {
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
+      if (diag && 8 * (r / 4) + (r % 4) > t) p = 0.f;
+      s[r] = p * (dp[r] - dsum_row);
     }
-    if (more) {
-      ks.store(smem + (cur ^ 1) * kTileBytes, tid);
-      vs.store(smem + (2 + (cur ^ 1)) * kTileBytes, tid);
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const bf16x8 dsb = pack8(s, 8 * cc);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = mfma(read_trans<D>(kt, fo, cc, db), dsb, acc[db]);
     }
+  };
+  auto body = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    wait_vm<(NS - 2) * LPS>();
     __syncthreads();
+    issue(sub + NS - 1, (ST + NS - 1) % NS);
+    compute(sub, stage_c);
+  };
+  for (int sub = 0; sub < n_sub; sub += NS) {
+    body(sub, std::integral_constant<int, 0>{});
+    if (sub + 1 >= n_sub) break;
+    body(sub + 1, std::integral_constant<int, 1>{});
+    if (sub + 2 >= n_sub) break;
+    body(sub + 2, std::integral_constant<int, 2>{});
+    if (sub + 3 >= n_sub) break;
+    body(sub + 3, std::integral_constant<int, 3>{});
   }
+  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
 
   if (it.slot >= 0) {
     store_frag<D>(partials + ((size_t)it.slot * Hq + head) * frag_floats<D>(), acc, wave, lane);
@@ -754,7 +891,8 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes + 4 * kStep * 4];
   float* stat = reinterpret_cast<float*>(smem + 4 * kTileBytes);
 
-  const int unit_idx = blockIdx.x / Hq, head = blockIdx.x % Hq;
+  int unit_idx, head;
+  decode_block(blockIdx.x, Hq, unit_idx, head);
   if (unit_idx >= hdr->n_col_units) return;
   const varlen_attn_unit it = units[unit_idx];
   const int kvh = head / (Hq / Hkv);
@@ -1052,7 +1190,7 @@ void launch_fwd(const varlen_attn_params* p, const void* q, const void* k, const
   const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   {
     ScopedKernelTimer timer(kFwd, stream);
-    fwd_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+    fwd_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
         R.row_part, N, Hq, Hkv, p->softmax_scale);
   }
@@ -1078,13 +1216,13 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   }
   {
     ScopedKernelTimer timer(kDkv, stream);
-    bwd_dkv_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+    bwd_dkv_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
         R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale);
   }
   {
     ScopedKernelTimer timer(kDq, stream);
-    bwd_dq_kernel<D><<<dim3((unsigned)L.max_units * Hq), kThreads, 0, stream>>>(
+    bwd_dq_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
         R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale);
   }
