@@ -124,7 +124,7 @@ typedef struct {
   size_t col_units_offset;
   size_t row_combine_offset;
   size_t col_combine_offset;
-  size_t dsum_offset;         /* fp32 D = rowsum(dO * O), [Hq, N] */
+  size_t dsum_offset;         /* fp32 D = rowsum(dO * O) [Hq, N], then LSE * log2(e) [Hq, N] */
   size_t row_partials_offset; /* fp32 partial results of cut row chains */
   size_t col_partials_offset; /* fp32 partial results of cut / grouped column chains */
   size_t total_bytes;

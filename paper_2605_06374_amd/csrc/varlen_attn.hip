@@ -190,11 +190,11 @@ __device__ __forceinline__ unsigned long long uniform64(const void* p) {
 // per-lane part of the address is a 32-bit offset fixed at init; the stage's first row goes
 // into the wave-uniform base, so a stage costs no vector arithmetic unless it runs past
 // `row_last` (then rows are clamped lane by lane).
-template <int D>
+template <int D, int ROWS = kSub>
 struct StageLoader {
   static constexpr int kRowsPerInstr = 1024 / (D * 2);      // 4 (D=128), 8 (D=64)
-  static constexpr int kInstr = kSub / kRowsPerInstr;       // 8, 4
-  static constexpr int kPerWave = kInstr / 4;               // 2, 1  (4 waves share a stage)
+  static constexpr int kInstr = ROWS / kRowsPerInstr;       // wave-level loads per stage
+  static constexpr int kPerWave = kInstr / 4;               // 4 waves share a stage
   int row_in_stage[kPerWave];
   unsigned col_bytes[kPerWave];
   unsigned voff[kPerWave];
@@ -210,16 +210,16 @@ struct StageLoader {
       voff[i] = (unsigned)r * stride_bytes + col_bytes[i];
     }
   }
-  // tile rows [row0, row0 + 32) of `base` -> LDS at `lds`; rows above row_last are clamped
+  // tile rows [row0, row0 + ROWS) of `base` -> LDS at `lds`; rows above row_last are clamped
   __device__ __forceinline__ void issue(const __bf16* base, int row0, int row_last, unsigned lds,
                                         int wave) const {
-    if (row0 + kSub - 1 <= row_last) {
-      const unsigned long long b = uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
+    const unsigned long long b =
+        uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
+    if (row0 + ROWS - 1 <= row_last) {
 #pragma unroll
       for (int i = 0; i < kPerWave; ++i)
         dma16(b, voff[i], __builtin_amdgcn_readfirstlane(lds + (wave + 4 * i) * 1024));
     } else {
-      const unsigned long long b = uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
 #pragma unroll
       for (int i = 0; i < kPerWave; ++i) {
         const int r = min(row_in_stage[i], row_last - row0);   // row_last >= row0 always
@@ -229,6 +229,18 @@ struct StageLoader {
     }
   }
 };
+
+// 64 consecutive floats (clamped at index `last`) -> 256 bytes of LDS, one wave-level load
+__device__ __forceinline__ void dma_floats64(const float* base, int first, int last, unsigned lds,
+                                             int lane) {
+  const unsigned long long b = uniform64(base + first);
+  unsigned voff = (unsigned)lane * 4;
+  if (first + 63 > last) voff = (unsigned)min(lane, last - first) * 4;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(voff), "s"(b), "s"(__builtin_amdgcn_readfirstlane(lds))
+               : "memory");
+}
 
 // per-lane byte offsets (inside a stage) of the two kinds of fragment reads
 template <int D>
@@ -718,11 +730,12 @@ fwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
 }
 
 // ----------------------------------------------------------------------------------------
-// Backward, step 0: D[h][t] = sum_c dO[t,h,c] * O[t,h,c]   (fp32)
+// Backward, step 0: D[h][t] = sum_c dO[t,h,c] * O[t,h,c]   (fp32), and LSE in log2 units
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads)
-rowdot_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, float* __restrict__ dsum,
+rowdot_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
+              const float* __restrict__ lse, float* __restrict__ dsum, float* __restrict__ lse2,
               int N, int Hq) {
   constexpr int LPR = D / 8;  // lanes per row
   const long long row = (long long)blockIdx.x * (kThreads / LPR) + threadIdx.x / LPR;
@@ -739,6 +752,7 @@ rowdot_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, floa
   if (part == 0 && row < (long long)N * Hq) {
     const int t = (int)(row / Hq), hh = (int)(row % Hq);
     dsum[(size_t)hh * N + t] = acc;
+    lse2[(size_t)hh * N + t] = lse[(size_t)hh * N + t] * kLog2e;  // exp2-domain LSE for dK/dV
   }
 }
 
@@ -880,16 +894,19 @@ template <int D>
 __global__ void __launch_bounds__(kThreads, 1)
 bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
-               const float* __restrict__ lse, const float* __restrict__ dsum,
+               const float* __restrict__ lse2, const float* __restrict__ dsum,
                const varlen_attn_plan_header* __restrict__ hdr,
                const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dk,
                __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
                float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int kTileBytes = kStep * D * 2;
-  // Q0 Q1 dO0 dO1 tiles, then lse2[2][kStep], dsum[2][kStep]
-  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes + 4 * kStep * 4];
-  float* stat = reinterpret_cast<float*>(smem + 4 * kTileBytes);
+  constexpr int NS = 4;                       // pipeline stages of kStep = 64 query rows
+  constexpr int kStageBytes = kStep * D * 2;
+  constexpr int kStatBytes = 512;             // lse2[64] then dsum[64], one copy per wave
+  using Loader = StageLoader<D, kStep>;
+  constexpr int LPS = 2 * Loader::kPerWave + 2;
+  // Q stages | dO stages | per-wave stat copies
+  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes + NS * 4 * kStatBytes];
 
   int unit_idx, head;
   decode_block(blockIdx.x, Hq, unit_idx, head);
@@ -903,6 +920,27 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const int my_kv = wave_kv0 + c;
   const bool kv_valid = my_kv < it.doc_end;
   const bool wave_active = wave_kv0 < it.doc_end;
+  const int n_steps = it.step_end - it.step_begin;
+
+  const __bf16* qbase = q + (size_t)head * D;
+  const __bf16* dobase = d_o + (size_t)head * D;
+  const float* lse_h = lse2 + (size_t)head * N;
+  const float* dsum_h = dsum + (size_t)head * N;
+  const unsigned lds_q = lds_addr_of(smem), lds_do = lds_q + NS * kStageBytes;
+  const unsigned lds_stat = lds_do + NS * kStageBytes + wave * kStatBytes;
+  const char* stat_base = smem + 2 * NS * kStageBytes + wave * kStatBytes;
+
+  Loader loader;
+  loader.init(wave, lane, (unsigned)((size_t)Hq * D * 2));
+  auto issue = [&](int st, int stage) {
+    const int q0 = it.row0 + kStep * (it.step_begin + min(st, n_steps - 1));
+    loader.issue(qbase, q0, it.doc_end - 1, lds_q + stage * kStageBytes, wave);
+    loader.issue(dobase, q0, it.doc_end - 1, lds_do + stage * kStageBytes, wave);
+    dma_floats64(lse_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes, lane);
+    dma_floats64(dsum_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes + 256, lane);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st, st);
 
   bf16x8 kf[KK], vf[KK];
 #pragma unroll
@@ -916,95 +954,181 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     kf[kk] = __builtin_bit_cast(bf16x8, t);
     vf[kk] = __builtin_bit_cast(bf16x8, u);
   }
+  FragOffsets<D> fo;
+  fo.init(lane);
+  wait_all_vm_visible();
 
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i) { dkacc[i] = f32x16(0.f); dvacc[i] = f32x16(0.f); }
 
-  const size_t q_stride = (size_t)Hq * D;
-  const __bf16* qbase = q + (size_t)head * D;
-  const __bf16* dobase = d_o + (size_t)head * D;
-
-  TileStager<D, kStep> qs, dos;
-  float stat_reg = 0.f;
-  auto stage_load = [&](int step) {
-    const int q0 = it.row0 + step * kStep;
-    qs.load(qbase, q_stride, q0, it.doc_end, tid);
-    dos.load(dobase, q_stride, q0, it.doc_end, tid);
-    if (tid < 2 * kStep) {
-      const int t = q0 + (tid % kStep);
-      if (tid < kStep) stat_reg = t < it.doc_end ? lse[(size_t)head * N + t] * kLog2e : 1e30f;
-      else stat_reg = t < it.doc_end ? dsum[(size_t)head * N + t] : 0.f;
+  // One 32-query block of a stage against this wave's 32 keys.  MASKED: the block may touch
+  // the diagonal or run past the document end (queries there are clamped duplicates).
+  auto block = [&](const char* qt, const char* dot, const char* st, int qb, int q0, auto masked_c) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    const int qb0 = q0 + 32 * qb;
+    if (MASKED && (qb0 + 31 < wave_kv0 || qb0 >= it.doc_end)) return;  // wave-uniform
+    f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s = mfma(lds_read_frag(qt, fo.row_frag[kk] + qb * 32 * D * 2), kf[kk], s);
+      dp = mfma(lds_read_frag(dot, fo.row_frag[kk] + qb * 32 * D * 2), vf[kk], dp);
     }
-  };
-  auto stage_store = [&](int buf) {
-    qs.store(smem + buf * kTileBytes, tid);
-    dos.store(smem + (2 + buf) * kTileBytes, tid);
-    if (tid < 2 * kStep) stat[(tid / kStep) * 2 * kStep + buf * kStep + (tid % kStep)] = stat_reg;
-  };
-  stage_load(it.step_begin);
-  stage_store(0);
-  __syncthreads();
-
-  for (int step = it.step_begin; step < it.step_end; ++step) {
-    const int cur = (step - it.step_begin) & 1;
-    const int q0 = it.row0 + step * kStep;
-    const char* qt = smem + cur * kTileBytes;
-    const char* dot = smem + (2 + cur) * kTileBytes;
-    const float* lse_t = stat + cur * kStep;
-    const float* ds_t = stat + 2 * kStep + cur * kStep;
-    const bool more = step + 1 < it.step_end;
-    if (more) stage_load(step + 1);
-    if (wave_active) {
+    f32x16 p;
 #pragma unroll
-      for (int qb = 0; qb < kStep / 32; ++qb) {
-        const int qb0 = q0 + 32 * qb;
-        // wave-uniform: block wholly above the diagonal for this wave, or past the document
-        if (qb0 + 31 < wave_kv0 || qb0 >= it.doc_end) continue;
-        f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+    for (int rq = 0; rq < 4; ++rq) {
+      const int rel = 32 * qb + 8 * rq + 4 * h;
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + rel * 4);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + rel * 4);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          bf16x8 a = lds_read_frag(qt, chunk_off<D>(32 * qb + c, 2 * kk + h));
-          s = mfma(a, kf[kk], s);
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * rq + e;
+        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -l4[e]));
+        if (MASKED) {
+          const int t = q0 + rel + e;
+          if (t < my_kv || t >= it.doc_end) pv = 0.f;
         }
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          bf16x8 a = lds_read_frag(dot, chunk_off<D>(32 * qb + c, 2 * kk + h));
-          dp = mfma(a, vf[kk], dp);
-        }
-        const bool diag = qb0 < wave_kv0 + 31;
-        f32x16 p;
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int rel = 32 * qb + 8 * rq + 4 * h;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + rel);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(ds_t + rel);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * rq + e;
-            float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -l4[e]));
-            if (diag && (q0 + rel + e) < my_kv) pv = 0.f;
-            p[r] = pv;
-            s[r] = pv * (dp[r] - d4[e]);
-          }
-        }
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 pb = pack8(p, 8 * cc);
-          const bf16x8 dsb = pack8(s, 8 * cc);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 a = lds_read_trans_frag<D>(dot, 32 * qb + 16 * cc, db, lane);
-            dvacc[db] = mfma(a, pb, dvacc[db]);
-            bf16x8 a2 = lds_read_trans_frag<D>(qt, 32 * qb + 16 * cc, db, lane);
-            dkacc[db] = mfma(a2, dsb, dkacc[db]);
-          }
-        }
+        p[r] = pv;
+        s[r] = pv * (dp[r] - d4[e]);
       }
     }
-    if (more) stage_store(cur ^ 1);
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const bf16x8 pb = pack8(p, 8 * cc);
+      const bf16x8 dsb = pack8(s, 8 * cc);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma(read_trans<D>(dot + qb * 32 * D * 2, fo, cc, db), pb, dvacc[db]);
+        dkacc[db] = mfma(read_trans<D>(qt + qb * 32 * D * 2, fo, cc, db), dsb, dkacc[db]);
+      }
+    }
+  };
+  // A whole 64-query stage away from the diagonal and the document end: the two 32-query
+  // blocks are software-pipelined by hand (this kernel runs one wave per SIMD, so nothing
+  // else hides LDS latency or overlaps the exponentials with the matrix pipe):
+  //   R0 | M1(0) + R1 | V(0) with M1(1) + T0 | M2(0) with V(1) + T1 | M2(1)
+  // R: row-fragment and statistics reads, T: transposed-fragment reads, M1: S and dP,
+  // V: P and dS on the vector ALU, M2: dV and dK.  The phase fences keep the compiler from
+  // sinking the reads back down to their first use.
+  auto stage_fast = [&](const char* qt, const char* dot, const char* st) {
+    bf16x8 qa[KK], da[KK], qb[KK], db_[KK];
+    bf16x8 tq0[2][DB], td0[2][DB], tq1[2][DB], td1[2][DB];
+    // ---- R0
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qa[kk] = lds_read_frag(qt, fo.row_frag[kk]);
+      da[kk] = lds_read_frag(dot, fo.row_frag[kk]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- M1(0) + R1
+    f32x16 s0 = f32x16(0.f), dp0 = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s0 = mfma(qa[kk], kf[kk], s0);
+      dp0 = mfma(da[kk], vf[kk], dp0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qb[kk] = lds_read_frag(qt, fo.row_frag[kk] + 32 * D * 2);
+      db_[kk] = lds_read_frag(dot, fo.row_frag[kk] + 32 * D * 2);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- V(0) with M1(1) + T0
+    f32x16 p0;
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + (8 * rq + 4 * h) * 4);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + (8 * rq + 4 * h) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * rq + e;
+        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], cs, -l4[e]));
+        p0[r] = pv;
+        s0[r] = pv * (dp0[r] - d4[e]);
+      }
+    }
+    bf16x8 pb0[2] = {pack8(p0, 0), pack8(p0, 8)}, dsb0[2] = {pack8(s0, 0), pack8(s0, 8)};
+    f32x16 s1 = f32x16(0.f), dp1 = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s1 = mfma(qb[kk], kf[kk], s1);
+      dp1 = mfma(db_[kk], vf[kk], dp1);
+    }
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        td0[cc][db] = read_trans<D>(dot, fo, cc, db);
+        tq0[cc][db] = read_trans<D>(qt, fo, cc, db);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- M2(0) with V(1) + T1
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma(td0[cc][db], pb0[cc], dvacc[db]);
+        dkacc[db] = mfma(tq0[cc][db], dsb0[cc], dkacc[db]);
+      }
+    f32x16 p1;
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + (32 + 8 * rq + 4 * h) * 4);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + (32 + 8 * rq + 4 * h) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * rq + e;
+        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], cs, -l4[e]));
+        p1[r] = pv;
+        s1[r] = pv * (dp1[r] - d4[e]);
+      }
+    }
+    bf16x8 pb1[2] = {pack8(p1, 0), pack8(p1, 8)}, dsb1[2] = {pack8(s1, 0), pack8(s1, 8)};
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        td1[cc][db] = read_trans<D>(dot + 32 * D * 2, fo, cc, db);
+        tq1[cc][db] = read_trans<D>(qt + 32 * D * 2, fo, cc, db);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- M2(1)
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma(td1[cc][db], pb1[cc], dvacc[db]);
+        dkacc[db] = mfma(tq1[cc][db], dsb1[cc], dkacc[db]);
+      }
+  };
+  auto body = [&](int st, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    wait_vm<(NS - 2) * LPS>();
     __syncthreads();
+    issue(st + NS - 1, (ST + NS - 1) % NS);
+    if (!wave_active) return;
+    const int step = it.step_begin + st;
+    const int q0 = it.row0 + kStep * step;
+    const char* qt = smem + ST * kStageBytes;
+    const char* dot = smem + (NS + ST) * kStageBytes;
+    const char* stt = stat_base + ST * 4 * kStatBytes;
+    if (step < 2 || q0 + kStep > it.doc_end) {
+      block(qt, dot, stt, 0, q0, std::true_type{});
+      block(qt, dot, stt, 1, q0, std::true_type{});
+    } else {
+      stage_fast(qt, dot, stt);
+    }
+  };
+  for (int st = 0; st < n_steps; st += NS) {
+    body(st, std::integral_constant<int, 0>{});
+    if (st + 1 >= n_steps) break;
+    body(st + 1, std::integral_constant<int, 1>{});
+    if (st + 2 >= n_steps) break;
+    body(st + 2, std::integral_constant<int, 2>{});
+    if (st + 3 >= n_steps) break;
+    body(st + 3, std::integral_constant<int, 3>{});
   }
+  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
 
   if (it.slot >= 0) {
     float* part = partials + ((size_t)it.slot * Hq + head) * 2 * frag_floats<D>();
@@ -1124,7 +1248,8 @@ bool layout_of(const varlen_attn_params* p, varlen_attn_workspace_layout* L, int
   L->col_units_offset = off; off = align_up(off + sizeof(varlen_attn_unit) * L->max_units, 256);
   L->row_combine_offset = off; off = align_up(off + sizeof(varlen_attn_combine_item) * L->max_combine, 256);
   L->col_combine_offset = off; off = align_up(off + sizeof(varlen_attn_combine_item) * L->max_combine, 256);
-  L->dsum_offset = off; off = align_up(off + sizeof(float) * (size_t)Hq * p->total_tokens, 256);
+  // D = rowsum(dO * O) [Hq, N], then LSE * log2(e) [Hq, N]
+  L->dsum_offset = off; off = align_up(off + 2 * sizeof(float) * (size_t)Hq * p->total_tokens, 256);
   L->row_partials_offset = off; off = align_up(off + fwd_part * Hq * L->max_row_slots, 256);
   L->col_partials_offset = off; off = align_up(off + 2 * frag * Hq * L->max_col_slots, 256);
   L->total_bytes = off;
@@ -1212,13 +1337,14 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   {
     ScopedKernelTimer timer(kRowdot, stream);
     rowdot_kernel<D><<<(unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), kThreads, 0, stream>>>(
-        (const __bf16*)o, (const __bf16*)d_o, R.dsum, N, Hq);
+        (const __bf16*)o, (const __bf16*)d_o, lse, R.dsum, R.dsum + (size_t)Hq * N, N, Hq);
   }
   {
     ScopedKernelTimer timer(kDkv, stream);
     bwd_dkv_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
-        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale);
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o,
+        R.dsum + (size_t)Hq * N, R.dsum, R.hdr, R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N,
+        Hq, Hkv, scale);
   }
   {
     ScopedKernelTimer timer(kDq, stream);

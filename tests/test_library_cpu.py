@@ -45,7 +45,7 @@ def test_workspace_bytes():
             L.dsum_offset, L.row_partials_offset, L.col_partials_offset, L.total_bytes]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert L.col_units_offset - L.row_units_offset >= 32 * L.max_units
-    assert L.row_partials_offset - L.dsum_offset >= 4 * 4 * 8192
+    assert L.row_partials_offset - L.dsum_offset >= 2 * 4 * 4 * 8192
     assert L.col_partials_offset - L.row_partials_offset >= (128 * 128 + 512) * 4 * 4 * L.max_row_slots
     assert L.total_bytes - L.col_partials_offset >= 2 * 128 * 128 * 4 * 4 * L.max_col_slots
     # grouped-query attention: every column tile needs a partial slot
