@@ -380,16 +380,20 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   int mode = sorted ? 0 : 1;
 #pragma unroll 1
   for (;;) {
-    // Every (document, tile) once: lanes take tile 0 of their own document, then whole waves
-    // sweep tiles 1.. of each longer document.  One call site for the per-tile code.
+    // Every (document, tile) once.  All waves walk all batches of 64 documents; tile 0 of a
+    // document is taken by one lane of the wave that owns the batch, and the further tiles of
+    // longer documents are swept by whole waves, the long documents dealt round-robin to the
+    // waves.  One call site for the per-tile code.
+    int long_rank = 0;
 #pragma unroll 1
-    for (int b0 = wave * 64; b0 < a.B; b0 += (kPlanThreads / 64) * 64) {
+    for (int b0 = 0; b0 < a.B; b0 += 64) {
       const int b = b0 + lane;
       int s = 0, e = 0;
       if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
       const int T = (e - s + kTile - 1) / kTile;
       unsigned long long pending = __ballot(T > 1);
-      int ss = s, ee = e, i = 0, TT = min(T, 1);
+      const bool own_batch = ((b0 >> 6) % (kPlanThreads / 64)) == wave;
+      int ss = s, ee = e, i = 0, TT = own_batch ? min(T, 1) : 0;
 #pragma unroll 1
       for (;;) {
 #pragma unroll 1
@@ -431,11 +435,19 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
           }
           i += 64;
         }
-        if (!pending) break;
-        const int src = __ffsll((long long)pending) - 1;
-        pending &= pending - 1;
-        ss = __shfl(s, src); ee = __shfl(e, src); TT = __shfl(T, src);
-        i = 1 + lane;
+        // next long document dealt to this wave
+        bool found = false;
+#pragma unroll 1
+        while (pending && !found) {
+          const int src = __ffsll((long long)pending) - 1;
+          pending &= pending - 1;
+          if ((long_rank++ % (kPlanThreads / 64)) == wave) {
+            ss = __shfl(s, src); ee = __shfl(e, src); TT = __shfl(T, src);
+            i = 1 + lane;
+            found = true;
+          }
+        }
+        if (!found) break;
       }
     }
     __syncthreads();
@@ -1147,19 +1159,19 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 // heads per output head; tensor 0 is multiplied by `scale0`.  Elementwise: thread t owns
 // float4 number t of the fragment.
 template <int D, int NT>
-__global__ void __launch_bounds__(kThreads)
-sum_combine_kernel(const int* __restrict__ n_items_ptr,
-                   const varlen_attn_combine_item* __restrict__ items,
-                   const float* __restrict__ partials, __bf16* __restrict__ out0,
-                   __bf16* __restrict__ out1, int Hin, int G, float scale0) {
+__device__ __forceinline__ void sum_combine(int block, int n_items,
+                                            const varlen_attn_combine_item* __restrict__ items,
+                                            const float* __restrict__ partials,
+                                            __bf16* __restrict__ out0, __bf16* __restrict__ out1,
+                                            int Hin, int G, float scale0) {
   constexpr int DB = D / 32;
   constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
   const int Hout = Hin / G;
-  const int sub = blockIdx.x % kBlocksPerItem;
-  int rest = blockIdx.x / kBlocksPerItem;
+  const int sub = block % kBlocksPerItem;
+  int rest = block / kBlocksPerItem;
   const int tensor = rest % NT; rest /= NT;
   const int idx = rest / Hout, oh = rest % Hout;
-  if (idx >= *n_items_ptr) return;
+  if (idx >= n_items) return;
   const varlen_attn_combine_item it = items[idx];
   const int t = sub * kThreads + threadIdx.x;
   const int lane = t & 63, rq = (t >> 6) & 3, db = (t >> 8) % DB, wave = (t >> 8) / DB;
@@ -1179,13 +1191,30 @@ sum_combine_kernel(const int* __restrict__ n_items_ptr,
       pack4(acc[0] * mul, acc[1] * mul, acc[2] * mul, acc[3] * mul);
 }
 
+// One launch for both backward reductions: the first `dkv_blocks` workgroups sum the
+// [dK | dV] partials (over chunks and the q heads of a group), the rest sum the dQ partials.
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
+                   const varlen_attn_combine_item* __restrict__ col_items,
+                   const varlen_attn_combine_item* __restrict__ row_items,
+                   const float* __restrict__ col_partials, const float* __restrict__ row_partials,
+                   __bf16* __restrict__ dk, __bf16* __restrict__ dv, __bf16* __restrict__ dq,
+                   int Hq, int Hkv, float scale, int dkv_blocks) {
+  if ((int)blockIdx.x < dkv_blocks)
+    sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale);
+  else
+    sum_combine<D, 1>(blockIdx.x - dkv_blocks, hdr->n_row_combine, row_items, row_partials, dq, nullptr,
+                      Hq, 1, scale);
+}
+
 // ----------------------------------------------------------------------------------------
 // Optional per-kernel timing (host-side HIP events only; off by default).
 // ----------------------------------------------------------------------------------------
-enum KernelId { kPlan = 0, kFwd, kFwdCombine, kRowdot, kDkv, kDq, kDkvCombine, kDqCombine, kNumKernels };
+enum KernelId { kPlan = 0, kFwd, kFwdCombine, kRowdot, kDkv, kDq, kBwdCombine, kNumKernels };
 const char* const kKernelNames[kNumKernels] = {
     "plan_kernel", "fwd_kernel", "fwd_combine_kernel", "rowdot_kernel", "bwd_dkv_kernel",
-    "bwd_dq_kernel", "bwd_dkv_combine_kernel", "bwd_dq_combine_kernel"};
+    "bwd_dq_kernel", "bwd_combine_kernel"};
 struct Profiler {
   std::mutex mu;
   bool enabled = false;
@@ -1354,14 +1383,13 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   }
   const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
   if (split || Hq != Hkv) {
-    ScopedKernelTimer timer(kDkvCombine, stream);
-    sum_combine_kernel<D, 2><<<dim3((unsigned)L.max_combine * Hkv * 2 * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
-        &R.hdr->n_col_combine, R.col_comb, R.col_part, (__bf16*)dk, (__bf16*)dv, Hq, Hq / Hkv, scale);
-  }
-  if (split) {
-    ScopedKernelTimer timer(kDqCombine, stream);
-    sum_combine_kernel<D, 1><<<dim3((unsigned)L.max_combine * Hq * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
-        &R.hdr->n_row_combine, R.row_comb, R.row_part, (__bf16*)dq, nullptr, Hq, 1, scale);
+    constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
+    const int dkv_blocks = L.max_combine * Hkv * 2 * kBlocksPerItem;
+    const int dq_blocks = split ? L.max_combine * Hq * kBlocksPerItem : 0;
+    ScopedKernelTimer timer(kBwdCombine, stream);
+    bwd_combine_kernel<D><<<dim3((unsigned)(dkv_blocks + dq_blocks)), kThreads, 0, stream>>>(
+        R.hdr, R.col_comb, R.row_comb, R.col_part, R.row_part, (__bf16*)dk, (__bf16*)dv, (__bf16*)dq,
+        Hq, Hkv, scale, dkv_blocks);
   }
 }
 
