@@ -295,8 +295,9 @@ inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)unit
 //
 // One workgroup.  For both directions (0: row chains for forward / dQ, 1: column chains for
 // dK / dV) it picks the chunk length, cuts every tile's chain into nearly equal chunks and
-// writes the units.  Chunk length: at least kMinChunkSteps, and long enough that (a) about
-// kTargetUnits (unit, head) pairs exist and (b) the partial-result slots fit the workspace.
+// writes the units.  Chunk length: at least kMinChunkSteps (growing to kMaxSmallChunkSteps as
+// a small microbatch fills the GPU), and long enough that (a) about kTargetUnits (unit, head)
+// pairs exist and (b) the partial-result slots fit the workspace.
 // Small microbatches (every unit is short anyway) are written in sweep order; large ones are
 // placed by a counting sort on cost, descending (longest job first).
 //
@@ -306,7 +307,8 @@ inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)unit
 // ----------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanBins = 1024;
-constexpr int kMinChunkSteps = 8;
+constexpr int kMinChunkSteps = 4;
+constexpr int kMaxSmallChunkSteps = 12;
 constexpr int kTargetUnits = 2048;
 constexpr int kNoSplitSteps = 1 << 28;
 constexpr long long kSortAboveSteps = 16384;  // (tile step, head) pairs; below: sweep order
@@ -367,7 +369,12 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       // 2 * steps / ch bounds the slots of the chains that get cut (each has > ch steps)
       const long long by_units = (long long)((steps[d] * a.Hq + kTargetUnits - 1) / kTargetUnits);
       const long long by_slots = (long long)((2 * steps[d] + a.slots_cap - 1) / a.slots_cap);
-      ch[d] = (int)max((long long)kMinChunkSteps, sorted ? by_units : max(by_units, by_slots));
+      // part-filled GPU: about one and a half rounds of units (512 resident workgroups), but
+      // never chunks so short that a unit's fixed cost (first loads, partial store) dominates
+      const long long by_fill = min((long long)kMaxSmallChunkSteps,
+                                    (long long)((3 * steps[d] * a.Hq + 1023) / 1024));
+      const long long floor_ch = max((long long)kMinChunkSteps, by_fill);
+      ch[d] = (int)max(floor_ch, sorted ? by_units : max(by_units, by_slots));
     }
   }
   if (sorted) {
