@@ -919,7 +919,10 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
                float scale) {
   constexpr int KK = D / 16, DB = D / 32;
-  constexpr int NS = 4;                       // pipeline stages of kStep = 64 query rows
+  // Two stages of kStep = 64 query rows: one stage of lookahead is a whole stage of compute
+  // (this kernel runs one workgroup per CU), and 64 KB of tiles keeps every LDS offset inside
+  // the 16-bit immediate of the read instructions.
+  constexpr int NS = 2;
   constexpr int kStageBytes = kStep * D * 2;
   constexpr int kStatBytes = 512;             // lse2[64] then dsum[64], one copy per wave
   using Loader = StageLoader<D, kStep>;
@@ -1142,10 +1145,6 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     body(st, std::integral_constant<int, 0>{});
     if (st + 1 >= n_steps) break;
     body(st + 1, std::integral_constant<int, 1>{});
-    if (st + 2 >= n_steps) break;
-    body(st + 2, std::integral_constant<int, 2>{});
-    if (st + 3 >= n_steps) break;
-    body(st + 3, std::integral_constant<int, 3>{});
   }
   wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
 
