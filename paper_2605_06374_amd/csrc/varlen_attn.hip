@@ -311,7 +311,7 @@ constexpr int kMinChunkSteps = 4;
 constexpr int kMaxSmallChunkSteps = 12;
 constexpr int kTargetUnits = 2048;
 constexpr int kNoSplitSteps = 1 << 28;
-constexpr long long kSortAboveSteps = 16384;  // (tile step, head) pairs; below: sweep order
+constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: sweep order
 
 struct PlanArgs {
   const int32_t* cu;
