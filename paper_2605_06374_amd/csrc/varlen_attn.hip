@@ -371,8 +371,9 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       const long long by_slots = (long long)((2 * steps[d] + a.slots_cap - 1) / a.slots_cap);
       // part-filled GPU: about one and a half rounds of units (512 resident workgroups), but
       // never chunks so short that a unit's fixed cost (first loads, partial store) dominates
-      const long long by_fill = min((long long)kMaxSmallChunkSteps,
-                                    (long long)((3 * steps[d] * a.Hq + 1023) / 1024));
+      // (dK/dV runs one workgroup per CU and its partials are twice as large: chunks twice as long)
+      const long long by_fill = min((long long)kMaxSmallChunkSteps * (d + 1),
+                                    (long long)((3 * (d + 1) * steps[d] * a.Hq + 1023) / 1024));
       const long long floor_ch = max((long long)kMinChunkSteps, by_fill);
       ch[d] = (int)max(floor_ch, sorted ? by_units : max(by_units, by_slots));
     }
@@ -568,7 +569,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
            const varlen_attn_plan_header* __restrict__ hdr,
            const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ o,
            float* __restrict__ lse, float* __restrict__ partials, int N, int Hq, int Hkv,
-           float scale) {
+           float scale, int max_units) {
   constexpr int KK = D / 16, DB = D / 32;
   constexpr int NS = 4;                              // pipeline stages of 32 keys
   constexpr int kStageBytes = kSub * D * 2;
@@ -577,8 +578,10 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
 
   int unit_idx, head;
   decode_block(blockIdx.x, Hq, unit_idx, head);
-  if (unit_idx >= hdr->n_row_units) return;
-  const varlen_attn_unit it = units[unit_idx];
+  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+  const int n_units = hdr->n_row_units;
+  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  if (unit_idx >= n_units) return;
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
@@ -786,7 +789,8 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
               const float* __restrict__ lse, const float* __restrict__ dsum,
               const varlen_attn_plan_header* __restrict__ hdr,
               const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dq,
-              float* __restrict__ partials, int N, int Hq, int Hkv, float scale) {
+              float* __restrict__ partials, int N, int Hq, int Hkv, float scale,
+              int max_units) {
   constexpr int KK = D / 16, DB = D / 32;
   constexpr int NS = 4;
   constexpr int kStageBytes = kSub * D * 2;
@@ -795,8 +799,10 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 
   int unit_idx, head;
   decode_block(blockIdx.x, Hq, unit_idx, head);
-  if (unit_idx >= hdr->n_row_units) return;
-  const varlen_attn_unit it = units[unit_idx];
+  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+  const int n_units = hdr->n_row_units;
+  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  if (unit_idx >= n_units) return;
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
@@ -917,7 +923,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                const varlen_attn_plan_header* __restrict__ hdr,
                const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dk,
                __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
-               float scale) {
+               float scale, int max_units) {
   constexpr int KK = D / 16, DB = D / 32;
   // Two stages of kStep = 64 query rows: one stage of lookahead is a whole stage of compute
   // (this kernel runs one workgroup per CU), and 64 KB of tiles keeps every LDS offset inside
@@ -932,8 +938,10 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 
   int unit_idx, head;
   decode_block(blockIdx.x, Hq, unit_idx, head);
-  if (unit_idx >= hdr->n_col_units) return;
-  const varlen_attn_unit it = units[unit_idx];
+  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+  const int n_units = hdr->n_col_units;
+  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  if (unit_idx >= n_units) return;
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;
@@ -1352,7 +1360,7 @@ void launch_fwd(const varlen_attn_params* p, const void* q, const void* k, const
     ScopedKernelTimer timer(kFwd, stream);
     fwd_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
-        R.row_part, N, Hq, Hkv, p->softmax_scale);
+        R.row_part, N, Hq, Hkv, p->softmax_scale, L.max_units);
   }
   if (!(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT)) {
     ScopedKernelTimer timer(kFwdCombine, stream);
@@ -1379,13 +1387,13 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
     bwd_dkv_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o,
         R.dsum + (size_t)Hq * N, R.dsum, R.hdr, R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N,
-        Hq, Hkv, scale);
+        Hq, Hkv, scale, L.max_units);
   }
   {
     ScopedKernelTimer timer(kDq, stream);
     bwd_dq_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
-        R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale);
+        R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale, L.max_units);
   }
   const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
   if (split || Hq != Hkv) {
