@@ -46,6 +46,10 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy 4 times, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="length-skew sweep: time each of the 64 microbatches of configuration 5 "
+                         "alone and fit T = c0 + beta * sum l(l+1)/2 (Eq. 1 at fixed N); prints a "
+                         "table and one JSON line, then exits")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -61,6 +65,9 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     binding.lib()  # fails loudly when the HIP library is missing
+
+    if args.sweep:
+        return sweep(args)
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -166,6 +173,62 @@ def main() -> int:
         "device": {"name": props.name, "cus": props.multi_processor_count},
     }
     print(json.dumps(out))
+    return 0
+
+
+def sweep(args) -> int:
+    """Configuration 5: 64 microbatches of 4096 tokens whose document-length medians run over
+    32..4096.  Section 5.2, Eq. 1 predicts T_MB = alpha * N + beta * sum l_i^2; at fixed N
+    that is an affine function of the causal pair count, which is what is fitted here."""
+    import numpy as np
+    import torch
+    from paper_2605_06374_amd import binding, workloads as W
+    from paper_2605_06374_amd.runner import DeviceProblem
+
+    reps, rows = 30, []
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(64):
+        w = W.config(5, microbatch=i)
+        p = DeviceProblem(w)
+        times = []
+        for r in range(reps + 5):
+            start.record()
+            p.forward()
+            p.backward(reuse_plan=True)
+            stop.record()
+            stop.synchronize()
+            if r >= 5:
+                times.append(start.elapsed_time(stop) * 1e3)
+        assert binding.varlen_attn_check(p.workspace) == binding.OK
+        t = float(np.median(times))
+        rows.append((i, len(w.lengths), sum(l * l for l in w.lengths), w.pairs, w.flops_fwd_bwd, t))
+        del p
+    pairs = np.array([r[3] for r in rows], dtype=np.float64)
+    t_us = np.array([r[5] for r in rows])
+    a = np.stack([np.ones_like(pairs), pairs], axis=1)
+    (c0, beta), *_ = np.linalg.lstsq(a, t_us, rcond=None)
+    pred = c0 + beta * pairs
+    mape = float(np.mean(np.abs(pred - t_us) / t_us) * 100)
+    r2 = float(1 - ((t_us - pred) ** 2).sum() / ((t_us - t_us.mean()) ** 2).sum())
+    print("| mb | docs | sum l^2 | pairs | GFLOP | median us | TFLOP/s | GB/s | predicted us |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for (i, nd, sl2, pr, fl, t), pt in zip(rows, pred):
+        w = W.config(5, microbatch=i)
+        print(f"| {i} | {nd} | {sl2} | {pr} | {fl / 1e9:.2f} | {t:.1f} | {fl / t / 1e6:.1f} | "
+              f"{w.algorithmic_bytes / t / 1e3:.0f} | {pt:.1f} |")
+    one4k = next(r[5] for r in rows if r[0] == 0)
+    four1k = DeviceProblem(W.custom("4x1024", [1024] * 4, 4, 4, 128, seed=5999))
+    tt = []
+    for r in range(reps + 5):
+        start.record(); four1k.forward(); four1k.backward(reuse_plan=True); stop.record()
+        stop.synchronize()
+        if r >= 5:
+            tt.append(start.elapsed_time(stop) * 1e3)
+    print(json.dumps({"sweep": "cfg5", "microbatches": 64, "fit_us": {"c0": round(float(c0), 2),
+                      "beta_per_pair": float(beta)}, "r2": round(r2, 4), "mape_percent": round(mape, 2),
+                      "one_4096_doc_us": round(one4k, 1), "four_1024_docs_us": round(float(np.median(tt)), 1),
+                      "time_ratio_4k_vs_4x1k": round(one4k / float(np.median(tt)), 2),
+                      "pair_ratio_4k_vs_4x1k": round(8390656 / 2099200, 3)}))
     return 0
 
 

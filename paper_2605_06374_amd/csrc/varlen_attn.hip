@@ -1195,10 +1195,19 @@ __device__ __forceinline__ void sum_combine(int block, int n_items,
   const size_t psize = NT * frag_floats<D>();
   const float* p0 = partials + ((size_t)it.slot0 * Hin + oh * G) * psize + tensor * frag_floats<D>() +
                     (size_t)t * 4;
+  // partial number j = ch * G + gh sits (ch * Hin + gh) partial sizes after the first; four
+  // loads are kept in flight, the additions stay in index order (deterministic)
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int ch = 0; ch < it.n_chunks; ++ch)
-    for (int gh = 0; gh < G; ++gh)
-      acc += *reinterpret_cast<const f32x4*>(p0 + ((size_t)ch * Hin + gh) * psize);
+  const int n_parts = it.n_chunks * G;
+  auto part = [&](int j) {
+    return *reinterpret_cast<const f32x4*>(p0 + ((size_t)(j / G) * Hin + (j % G)) * psize);
+  };
+  int j = 0;
+  for (; j + 4 <= n_parts; j += 4) {
+    const f32x4 x0 = part(j), x1 = part(j + 1), x2 = part(j + 2), x3 = part(j + 3);
+    acc += x0; acc += x1; acc += x2; acc += x3;
+  }
+  for (; j < n_parts; ++j) acc += part(j);
   const float mul = tensor == 0 ? scale0 : 1.0f;
   __bf16* out = tensor == 0 ? out0 : out1;
   *reinterpret_cast<uint2*>(out + ((size_t)my_row * Hout + oh) * D + 32 * db + 8 * rq + 4 * h) =
