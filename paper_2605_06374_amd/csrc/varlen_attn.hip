@@ -295,9 +295,11 @@ inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)unit
 //
 // One workgroup.  For both directions (0: row chains for forward / dQ, 1: column chains for
 // dK / dV) it picks the chunk length, cuts every tile's chain into nearly equal chunks and
-// writes the units.  Chunk length: at least kMinChunkSteps (growing to kMaxSmallChunkSteps as
-// a small microbatch fills the GPU), and long enough that (a) about kTargetUnits (unit, head)
-// pairs exist and (b) the partial-result slots fit the workspace.
+// writes the units.  Chunk length: at least kMinChunkSteps; on a microbatch whose tiles do not
+// fill the GPU by themselves, just long enough that all (unit, head) pairs are resident at
+// once (kResidentGroups workgroups: one round, no second wave of stragglers); otherwise long
+// enough that about kTargetUnits pairs exist; and always such that the partial-result slots
+// fit the workspace.
 // Small microbatches (every unit is short anyway) are written in sweep order; large ones are
 // placed by a counting sort on cost, descending (longest job first).
 //
@@ -308,7 +310,7 @@ inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)unit
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanBins = 1024;
 constexpr int kMinChunkSteps = 4;
-constexpr int kMaxSmallChunkSteps = 12;
+constexpr int kResidentGroups = 512;  // 256 CUs x 2 workgroups (forward, dQ)
 constexpr int kTargetUnits = 2048;
 constexpr int kNoSplitSteps = 1 << 28;
 constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: sweep order
@@ -328,18 +330,20 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   __shared__ int cursor[2][kPlanBins];
   __shared__ int wsum[kPlanThreads / 64];
   __shared__ unsigned long long pairs, steps[2];
+  __shared__ int n_tiles;
   __shared__ int split[2], n_units[2], n_slots[2], n_comb[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* cu = a.cu;
   if (tid == 0) {
     bad = (cu[0] != 0) || (cu[a.B] != a.N);
     pairs = steps[0] = steps[1] = 0;
+    n_tiles = 0;
   }
   if (tid < 2) split[tid] = n_units[tid] = n_slots[tid] = n_comb[tid] = 0;
   __syncthreads();
   {
     unsigned long long my_pairs = 0, my_r = 0, my_c = 0;
-    int my_bad = 0;
+    int my_bad = 0, my_tiles = 0;
 #pragma unroll 1
     for (int b = tid; b < a.B; b += kPlanThreads) {
       const long long l = (long long)cu[b + 1] - cu[b];
@@ -348,9 +352,10 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       const long long T = (l + kTile - 1) / kTile, S = (l + kStep - 1) / kStep;
       my_r += (unsigned long long)(T * (T - 1) + S);
       my_c += (unsigned long long)(T * S - T * (T - 1));
+      my_tiles += (int)T;
     }
     if (my_bad) bad = 1;
-    if (my_pairs) { atomicAdd(&pairs, my_pairs); atomicAdd(&steps[0], my_r); atomicAdd(&steps[1], my_c); }
+    if (my_pairs) { atomicAdd(&pairs, my_pairs); atomicAdd(&steps[0], my_r); atomicAdd(&steps[1], my_c); atomicAdd(&n_tiles, my_tiles); }
   }
   __syncthreads();
   varlen_attn_plan_header* hdr = a.hdr;
@@ -369,11 +374,13 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       // 2 * steps / ch bounds the slots of the chains that get cut (each has > ch steps)
       const long long by_units = (long long)((steps[d] * a.Hq + kTargetUnits - 1) / kTargetUnits);
       const long long by_slots = (long long)((2 * steps[d] + a.slots_cap - 1) / a.slots_cap);
-      // part-filled GPU: about one and a half rounds of units (512 resident workgroups), but
-      // never chunks so short that a unit's fixed cost (first loads, partial store) dominates
-      // (dK/dV runs one workgroup per CU and its partials are twice as large: chunks twice as long)
-      const long long by_fill = min((long long)kMaxSmallChunkSteps * (d + 1),
-                                    (long long)((3 * (d + 1) * steps[d] * a.Hq + 1023) / 1024));
+      // Units of one head ~ steps / ch + tiles / 2 (a cut chain rarely divides evenly).  If
+      // the tiles leave room, take the shortest chunks that keep every unit resident at once;
+      // dK/dV partials are twice as large and its kernel is insensitive here: twice as long.
+      const long long room = kResidentGroups / a.Hq - n_tiles / 2;
+      long long by_fill = 0;
+      if (room >= kResidentGroups / a.Hq / 4 && room > 0)
+        by_fill = (d + 1) * (((long long)steps[d] + room - 1) / room);
       const long long floor_ch = max((long long)kMinChunkSteps, by_fill);
       ch[d] = (int)max(floor_ch, sorted ? by_units : max(by_units, by_slots));
     }
