@@ -759,41 +759,16 @@ fwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
 }
 
 // ----------------------------------------------------------------------------------------
-// Backward, step 0: D[h][t] = sum_c dO[t,h,c] * O[t,h,c]   (fp32), and LSE in log2 units
-// ----------------------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(kThreads)
-rowdot_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
-              const float* __restrict__ lse, float* __restrict__ dsum, float* __restrict__ lse2,
-              int N, int Hq) {
-  constexpr int LPR = D / 8;  // lanes per row
-  const long long row = (long long)blockIdx.x * (kThreads / LPR) + threadIdx.x / LPR;
-  const int part = threadIdx.x % LPR;
-  float acc = 0.f;
-  if (row < (long long)N * Hq) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + (size_t)row * D + part * 8);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(d_o + (size_t)row * D + part * 8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
-  }
-#pragma unroll
-  for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-  if (part == 0 && row < (long long)N * Hq) {
-    const int t = (int)(row / Hq), hh = (int)(row % Hq);
-    dsum[(size_t)hh * N + t] = acc;
-    lse2[(size_t)hh * N + t] = lse[(size_t)hh * N + t] * kLog2e;  // exp2-domain LSE for dK/dV
-  }
-}
-
-// ----------------------------------------------------------------------------------------
-// Backward, dQ.  Same decomposition as the forward: one workgroup per (row unit, q head).
+// Backward, dQ (first backward kernel).  Same decomposition as the forward: one workgroup per
+// (row unit, q head).  Its prologue also computes D = rowsum(dO * O) for its rows.
 // S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - D), dQ^T += K^T dS^T.
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads, 2)
 bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-              const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
-              const float* __restrict__ lse, const float* __restrict__ dsum,
+              const __bf16* __restrict__ v, const __bf16* __restrict__ o,
+              const __bf16* __restrict__ d_o, const float* __restrict__ lse,
+              float* __restrict__ dsum, float* __restrict__ lse2_out,
               const varlen_attn_plan_header* __restrict__ hdr,
               const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dq,
               float* __restrict__ partials, int N, int Hq, int Hkv, float scale,
@@ -838,21 +813,33 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st) issue(st, st);
 
+  // Q and dO fragments stay in registers; the O fragments are only needed for
+  // D = rowsum(dO * O): each lane holds half of its row's columns, the other half-wave the rest.
   bf16x8 qf[KK], dof[KK];
+  float d_part = 0.f;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    uint4 t = {0, 0, 0, 0}, u = {0, 0, 0, 0};
+    uint4 t = {0, 0, 0, 0}, u = {0, 0, 0, 0}, w = {0, 0, 0, 0};
     if (row_valid) {
       const size_t off = ((size_t)my_row * Hq + head) * D + 16 * kk + 8 * h;
       t = *reinterpret_cast<const uint4*>(q + off);
       u = *reinterpret_cast<const uint4*>(d_o + off);
+      w = *reinterpret_cast<const uint4*>(o + off);
     }
     qf[kk] = __builtin_bit_cast(bf16x8, t);
     dof[kk] = __builtin_bit_cast(bf16x8, u);
+    const bf16x8 of = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d_part += (float)dof[kk][e] * (float)of[e];
   }
+  const float dsum_row = half_sum(d_part);
   // rows past the document end get LSE = +huge so that their P is exactly 0
   const float lse2 = row_valid ? lse[(size_t)head * N + my_row] * kLog2e : 1e30f;
-  const float dsum_row = row_valid ? dsum[(size_t)head * N + my_row] : 0.f;
+  // the unit that starts the chain publishes D and LSE * log2(e) for the dK/dV kernel
+  if (it.step_begin == 0 && row_valid && h == 0) {
+    dsum[(size_t)head * N + my_row] = dsum_row;
+    lse2_out[(size_t)head * N + my_row] = lse2;
+  }
   FragOffsets<D> fo;
   fo.init(lane);
   wait_all_vm_visible();
@@ -1241,10 +1228,10 @@ bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
 // ----------------------------------------------------------------------------------------
 // Optional per-kernel timing (host-side HIP events only; off by default).
 // ----------------------------------------------------------------------------------------
-enum KernelId { kPlan = 0, kFwd, kFwdCombine, kRowdot, kDkv, kDq, kBwdCombine, kNumKernels };
+enum KernelId { kPlan = 0, kFwd, kFwdCombine, kDq, kDkv, kBwdCombine, kNumKernels };
 const char* const kKernelNames[kNumKernels] = {
-    "plan_kernel", "fwd_kernel", "fwd_combine_kernel", "rowdot_kernel", "bwd_dkv_kernel",
-    "bwd_dq_kernel", "bwd_combine_kernel"};
+    "plan_kernel", "fwd_kernel", "fwd_combine_kernel", "bwd_dq_kernel", "bwd_dkv_kernel",
+    "bwd_combine_kernel"};
 struct Profiler {
   std::mutex mu;
   bool enabled = false;
@@ -1391,25 +1378,20 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
                 const Regions& R, const varlen_attn_workspace_layout& L, hipStream_t stream) {
   const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   const float scale = p->softmax_scale;
-  const long long rows = (long long)N * Hq;
-  constexpr int kRowsPerBlock = kThreads / (D / 8);
+  float* lse2 = R.dsum + (size_t)Hq * N;
   {
-    ScopedKernelTimer timer(kRowdot, stream);
-    rowdot_kernel<D><<<(unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), kThreads, 0, stream>>>(
-        (const __bf16*)o, (const __bf16*)d_o, lse, R.dsum, R.dsum + (size_t)Hq * N, N, Hq);
+    // also writes D = rowsum(dO * O) and LSE * log2(e), which the dK/dV kernel reads
+    ScopedKernelTimer timer(kDq, stream);
+    bwd_dq_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)o, (const __bf16*)d_o,
+        lse, R.dsum, lse2, R.hdr, R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale,
+        L.max_units);
   }
   {
     ScopedKernelTimer timer(kDkv, stream);
     bwd_dkv_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o,
-        R.dsum + (size_t)Hq * N, R.dsum, R.hdr, R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N,
-        Hq, Hkv, scale, L.max_units);
-  }
-  {
-    ScopedKernelTimer timer(kDq, stream);
-    bwd_dq_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse, R.dsum, R.hdr,
-        R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale, L.max_units);
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse2, R.dsum, R.hdr,
+        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale, L.max_units);
   }
   const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
   if (split || Hq != Hkv) {
