@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 #include <mutex>
 #include <vector>
 
@@ -42,6 +43,17 @@ constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleTau = 8.0f;  // running max may lag by up to 2^8 before O is rescaled
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose body may hold
+// scheduling fences (an ordinary loop that holds one is not unrolled).
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // ----------------------------------------------------------------------------------------
 // LDS tiles: row-major [rows][D] bf16, addressed in 16-byte chunks with an XOR swizzle that
@@ -1032,90 +1044,86 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // else hides LDS latency or overlaps the exponentials with the matrix pipe):
   //   R0 | M1(0) + R1 | V(0) with M1(1) + T0 | M2(0) with V(1) + T1 | M2(1)
   // R: row-fragment and statistics reads, T: transposed-fragment reads, M1: S and dP,
-  // V: P and dS on the vector ALU, M2: dV and dK.  The phase fences keep the compiler from
-  // sinking the reads back down to their first use.
+  // V: P and dS on the vector ALU, M2: dV and dK.  Each matrix instruction is written next to
+  // the vector and LDS work that should ride on it, and the fences keep that order.
   auto stage_fast = [&](const char* qt, const char* dot, const char* st) {
+    constexpr int EPM = 16 / (2 * KK);  // score elements handled beside each matrix instruction
     bf16x8 qa[KK], da[KK], qb[KK], db_[KK];
     bf16x8 tq0[2][DB], td0[2][DB], tq1[2][DB], td1[2][DB];
+    f32x4 l0[4], d0[4], l1[4], d1[4];
+    // softmax of element r of one block: p = 2^(s cs - lse2), ds = p (dp - D)
+    auto soft = [&](f32x16& sv, const f32x16& dpv, f32x16& pv, const f32x4* l, const f32x4* dd, int r) {
+      const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], cs, -l[r >> 2][r & 3]));
+      pv[r] = e;
+      sv[r] = e * (dpv[r] - dd[r >> 2][r & 3]);
+    };
     // ---- R0
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       qa[kk] = lds_read_frag(qt, fo.row_frag[kk]);
       da[kk] = lds_read_frag(dot, fo.row_frag[kk]);
     }
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      l0[rq] = *reinterpret_cast<const f32x4*>(st + (8 * rq + 4 * h) * 4);
+      d0[rq] = *reinterpret_cast<const f32x4*>(st + 256 + (8 * rq + 4 * h) * 4);
+    }
     __builtin_amdgcn_sched_barrier(0);
     // ---- M1(0) + R1
     f32x16 s0 = f32x16(0.f), dp0 = f32x16(0.f);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
+    static_for<KK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
       s0 = mfma(qa[kk], kf[kk], s0);
-      dp0 = mfma(da[kk], vf[kk], dp0);
-    }
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
       qb[kk] = lds_read_frag(qt, fo.row_frag[kk] + 32 * D * 2);
+      if (kk < 4) l1[kk] = *reinterpret_cast<const f32x4*>(st + (32 + 8 * kk + 4 * h) * 4);
+      __builtin_amdgcn_sched_barrier(0);
+      dp0 = mfma(da[kk], vf[kk], dp0);
       db_[kk] = lds_read_frag(dot, fo.row_frag[kk] + 32 * D * 2);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+      if (kk < 4) d1[kk] = *reinterpret_cast<const f32x4*>(st + 256 + (32 + 8 * kk + 4 * h) * 4);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     // ---- V(0) with M1(1) + T0
-    f32x16 p0;
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + (8 * rq + 4 * h) * 4);
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + (8 * rq + 4 * h) * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 4 * rq + e;
-        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], cs, -l4[e]));
-        p0[r] = pv;
-        s0[r] = pv * (dp0[r] - d4[e]);
-      }
-    }
-    bf16x8 pb0[2] = {pack8(p0, 0), pack8(p0, 8)}, dsb0[2] = {pack8(s0, 0), pack8(s0, 8)};
-    f32x16 s1 = f32x16(0.f), dp1 = f32x16(0.f);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
+    f32x16 p0, s1 = f32x16(0.f), dp1 = f32x16(0.f);
+    bf16x8 pb0[2], dsb0[2];
+    static_for<KK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
       s1 = mfma(qb[kk], kf[kk], s1);
+#pragma unroll
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * 2 * kk + e);
+      td0[kk / DB][kk % DB] = read_trans<D>(dot, fo, kk / DB, kk % DB);
+      __builtin_amdgcn_sched_barrier(0);
       dp1 = mfma(db_[kk], vf[kk], dp1);
-    }
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        td0[cc][db] = read_trans<D>(dot, fo, cc, db);
-        tq0[cc][db] = read_trans<D>(qt, fo, cc, db);
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * (2 * kk + 1) + e);
+      tq0[kk / DB][kk % DB] = read_trans<D>(qt, fo, kk / DB, kk % DB);
+      if ((kk + 1) * 2 * EPM % 8 == 0) {
+        constexpr int i = (kk + 1) * 2 * EPM / 8 - 1;
+        pb0[i] = pack8(p0, 8 * i);
+        dsb0[i] = pack8(s0, 8 * i);
       }
-    __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     // ---- M2(0) with V(1) + T1
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        dvacc[db] = mfma(td0[cc][db], pb0[cc], dvacc[db]);
-        dkacc[db] = mfma(tq0[cc][db], dsb0[cc], dkacc[db]);
-      }
     f32x16 p1;
+    bf16x8 pb1[2], dsb1[2];
+    static_for<2 * DB>([&](auto j_c) {
+      constexpr int j = decltype(j_c)::value;
+      dvacc[j % DB] = mfma(td0[j / DB][j % DB], pb0[j / DB], dvacc[j % DB]);
 #pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + (32 + 8 * rq + 4 * h) * 4);
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + (32 + 8 * rq + 4 * h) * 4);
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * 2 * j + e);
+      td1[j / DB][j % DB] = read_trans<D>(dot + 32 * D * 2, fo, j / DB, j % DB);
+      __builtin_amdgcn_sched_barrier(0);
+      dkacc[j % DB] = mfma(tq0[j / DB][j % DB], dsb0[j / DB], dkacc[j % DB]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 4 * rq + e;
-        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], cs, -l4[e]));
-        p1[r] = pv;
-        s1[r] = pv * (dp1[r] - d4[e]);
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * (2 * j + 1) + e);
+      tq1[j / DB][j % DB] = read_trans<D>(qt + 32 * D * 2, fo, j / DB, j % DB);
+      if ((j + 1) * 2 * EPM % 8 == 0) {
+        constexpr int i = (j + 1) * 2 * EPM / 8 - 1;
+        pb1[i] = pack8(p1, 8 * i);
+        dsb1[i] = pack8(s1, 8 * i);
       }
-    }
-    bf16x8 pb1[2] = {pack8(p1, 0), pack8(p1, 8)}, dsb1[2] = {pack8(s1, 0), pack8(s1, 8)};
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        td1[cc][db] = read_trans<D>(dot + 32 * D * 2, fo, cc, db);
-        tq1[cc][db] = read_trans<D>(qt + 32 * D * 2, fo, cc, db);
-      }
-    __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     // ---- M2(1)
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc)
