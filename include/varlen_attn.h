@@ -68,6 +68,11 @@ extern "C" {
                                          (bit-identical results under repacking), at the
                                          price of idle compute units on short microbatches */
 
+/* Tuning: bits 8..15 of flags = longest chunk of a row chain, bits 16..23 = of a column chain,
+ * in steps (0 = chosen by the plan from the microbatch; the plan still lengthens a value
+ * whose partial results would not fit the workspace). */
+#define VARLEN_ATTN_FLAG_CHUNK_STEPS(row, col) ((((row) & 0xFF) << 8) | (((col) & 0xFF) << 16))
+
 typedef struct {
   int32_t total_tokens;  /* N   >= 1 */
   int32_t num_docs;      /* B   >= 1; cu_seqlens has B + 1 entries */

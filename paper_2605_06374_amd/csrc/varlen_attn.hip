@@ -330,6 +330,7 @@ constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: 
 struct PlanArgs {
   const int32_t* cu;
   int B, N, Hq, g, shift, no_split;
+  int force_ch[2];  // > 0: chunk length given by the caller (tuning), per direction
   varlen_attn_plan_header* hdr;
   varlen_attn_unit* units[2];
   varlen_attn_combine_item* comb[2];
@@ -395,6 +396,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         by_fill = (d + 1) * (((long long)steps[d] + room - 1) / room);
       const long long floor_ch = max((long long)kMinChunkSteps, by_fill);
       ch[d] = (int)max(floor_ch, sorted ? by_units : max(by_units, by_slots));
+      if (a.force_ch[d] > 0) ch[d] = (int)max((long long)a.force_ch[d], sorted ? 1 : by_slots);
     }
   }
   if (sorted) {
@@ -1353,6 +1355,8 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.cu = cu; a.B = p->num_docs; a.N = p->total_tokens; a.Hq = p->num_q_heads;
   a.g = p->num_q_heads / p->num_kv_heads; a.shift = shift;
   a.no_split = (p->flags & VARLEN_ATTN_FLAG_NO_SPLIT) ? 1 : 0;
+  a.force_ch[0] = (p->flags >> 8) & 0xFF;
+  a.force_ch[1] = (p->flags >> 16) & 0xFF;
   a.hdr = R.hdr; a.units[0] = R.row_units; a.units[1] = R.col_units;
   a.comb[0] = R.row_comb; a.comb[1] = R.col_comb;
   a.max_units = L.max_units; a.max_combine = L.max_combine;
