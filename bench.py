@@ -46,6 +46,9 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy 4 times, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--mfma-rate", action="store_true",
+                    help="also time a pure bf16 MFMA kernel with constant and with hashed operands "
+                         "(what the matrix pipe sustains on this box) and report both")
     ap.add_argument("--sweep", action="store_true",
                     help="length-skew sweep: time each of the 64 microbatches of configuration 5 "
                          "alone and fit T = c0 + beta * sum l(l+1)/2 (Eq. 1 at fixed N); prints a "
@@ -124,6 +127,13 @@ def main() -> int:
                     "algorithmic_flops_per_launch": alg,
                     "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
 
+    mfma_rate = None
+    if args.mfma_rate:
+        scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
+        mfma_rate = {"unit": "TFLOP/s",
+                     "constant_operands": round(binding.varlen_attn_mfma_rate(False, 20000, scratch.data_ptr()), 1),
+                     "hashed_operands": round(binding.varlen_attn_mfma_rate(True, 20000, scratch.data_ptr()), 1)}
+
     # ---- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None
     if not args.no_cpu_baseline:
@@ -172,6 +182,8 @@ def main() -> int:
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in kernels.items()},
         "device": {"name": props.name, "cus": props.multi_processor_count},
     }
+    if mfma_rate:
+        out["mfma_rate"] = mfma_rate
     print(json.dumps(out))
     return 0
 

@@ -187,6 +187,16 @@ int varlen_attn_profile(int enable);
  * Blocks the host. */
 int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity);
 
+/* Measurement aid for benchmarks: runs, on `hip_stream`, a kernel that issues nothing but
+ * bf16 MFMA 32x32x16 from registers on every SIMD (2^4 * `iterations` instructions per wave,
+ * 8 waves per compute unit), twice, and writes the rate of the second run to the HOST float
+ * `tflops`.  random_operands = 0: all operands 1.0; 1: hashed signs and mantissas, which is
+ * what the matrix pipe sustains on real data.  `device_scratch`: any 4 writable device
+ * bytes (practically never written).  Blocks the host.  Returns VARLEN_ATTN_OK,
+ * VARLEN_ATTN_INVALID_ARG or VARLEN_ATTN_LAUNCH_FAILED. */
+int varlen_attn_mfma_rate(int random_operands, int iterations, void* device_scratch,
+                          void* hip_stream, float* tflops);
+
 /* Static text for a status code; never NULL. */
 const char* varlen_attn_status_string(int status);
 

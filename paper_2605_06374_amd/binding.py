@@ -95,6 +95,9 @@ def lib() -> ctypes.CDLL:
         L.varlen_attn_check.argtypes = [vp, vp]
         L.varlen_attn_status_string.restype = ctypes.c_char_p
         L.varlen_attn_status_string.argtypes = [ctypes.c_int]
+        L.varlen_attn_mfma_rate.restype = ctypes.c_int
+        L.varlen_attn_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
+                                            ctypes.POINTER(ctypes.c_float)]
         L.varlen_attn_profile.restype = ctypes.c_int
         L.varlen_attn_profile.argtypes = [ctypes.c_int]
         L.varlen_attn_profile_read.restype = ctypes.c_int
@@ -176,6 +179,15 @@ def varlen_attn_profile_read():
     n = int(lib().varlen_attn_profile_read(buf, 16))
     check(min(n, 0))
     return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n)}
+
+
+def varlen_attn_mfma_rate(random_operands: bool, iterations: int, device_scratch, stream=None) -> float:
+    """TFLOP/s of a pure bf16 MFMA 32x32x16 kernel (see the header); blocks the host."""
+    out = ctypes.c_float(0.0)
+    check(lib().varlen_attn_mfma_rate(int(bool(random_operands)), int(iterations),
+                                      ctypes.c_void_p(int(device_scratch)),
+                                      ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
+    return float(out.value)
 
 
 def varlen_attn_status_string(status: int) -> str:

@@ -1236,6 +1236,45 @@ bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
 }
 
 // ----------------------------------------------------------------------------------------
+// Measurement aid: nothing but bf16 MFMA 32x32x16 on every SIMD (two waves each, four
+// independent accumulator chains per wave), operands held in registers.  `random_operands`
+// fills A and B with hashed mantissas and signs instead of 1.0: what the matrix pipe sustains
+// then is the practical ceiling for kernels whose operands are real data.
+// ----------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads, 2)
+mfma_rate_kernel(float* __restrict__ out, int iters, int random_operands) {
+  bf16x8 a[4], b[4];
+  f32x16 c[4];
+  unsigned x = (blockIdx.x * kThreads + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    unsigned w[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x = x * 1664525u + 1013904223u;
+      const unsigned y = x ^ (x >> 15);
+      // 1.0 with hashed sign and 7-bit mantissa in each half word, or plain 1.0
+      w[e] = random_operands ? (0x3f803f80u ^ (y & 0x807f807fu)) : 0x3f803f80u;
+    }
+    a[u] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
+    b[u] = __builtin_bit_cast(bf16x8, uint4{w[4], w[5], w[6], w[7]});
+    c[u] = f32x16(0.f);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) c[u] = mfma(a[u], b[(u + rep) & 3], c[u]);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += c[u][r];
+  if (sum == 12345.678f) out[0] = sum;  // keeps the chains alive; practically never true
+}
+
+// ----------------------------------------------------------------------------------------
 // Optional per-kernel timing (host-side HIP events only; off by default).
 // ----------------------------------------------------------------------------------------
 enum KernelId { kPlan = 0, kFwd, kFwdCombine, kDq, kDkv, kBwdCombine, kNumKernels };
@@ -1528,6 +1567,36 @@ int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity) {
     ++n;
   }
   return n;
+}
+
+int varlen_attn_mfma_rate(int random_operands, int iterations, void* device_scratch,
+                          void* hip_stream, float* tflops) {
+  if (!device_scratch || !tflops || iterations < 1 || iterations > (1 << 24))
+    return VARLEN_ATTN_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return VARLEN_ATTN_LAUNCH_FAILED;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
+  const unsigned grid = 2u * (unsigned)cus;
+  float ms = 0.f;
+  bool ok = true;
+  for (int pass = 0; pass < 2 && ok; ++pass) {   // the first pass warms the clocks up
+    ok = hipEventRecord(e0, stream) == hipSuccess;
+    mfma_rate_kernel<<<dim3(grid), kThreads, 0, stream>>>(static_cast<float*>(device_scratch),
+                                                          iterations, random_operands);
+    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
+         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
+  const double flops = (double)grid * (kThreads / 64) * (double)iterations * 16.0 * 32768.0;
+  *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+  return VARLEN_ATTN_OK;
 }
 
 const char* varlen_attn_status_string(int status) {

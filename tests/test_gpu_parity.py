@@ -338,3 +338,15 @@ def test_cost_follows_sum_of_squares_not_n_squared(gpu):
     a = oplan.causal_tile_pairs([0, 4096], 128, 64)
     b = oplan.causal_tile_pairs([0, 1024, 2048, 3072, 4096], 128, 64)
     assert 3.5 < a / b < 4.0
+
+
+def test_mfma_rate_probe_runs(gpu):
+    """The measurement aid returns a plausible rate and rejects bad arguments."""
+    import torch
+    from paper_2605_06374_amd import binding
+    scratch = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    for hashed in (False, True):
+        rate = binding.varlen_attn_mfma_rate(hashed, 2000, scratch.data_ptr())
+        assert 50.0 < rate < 2600.0, rate
+    with pytest.raises(RuntimeError):
+        binding.varlen_attn_mfma_rate(False, 0, scratch.data_ptr())
