@@ -27,9 +27,9 @@ PEAK_HBM_GBS = 8000.0
 # device copy of --calibrate-copy (profiles/kernel_stats_and_counters_cfg2_7b_tp8_8k.md);
 # None for a (workload, kernel) pair that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2_7b_tp8_8k", "bwd_dkv_kernel"): 146.3e6,
-    ("cfg2_7b_tp8_8k", "bwd_dq_kernel"): 102.5e6,
-    ("cfg2_7b_tp8_8k", "fwd_kernel"): 86.6e6,
+    ("cfg2_7b_tp8_8k", "bwd_dkv_kernel"): 85.4e6,
+    ("cfg2_7b_tp8_8k", "bwd_dq_kernel"): 101.8e6,
+    ("cfg2_7b_tp8_8k", "fwd_kernel"): 73.3e6,
 }
 
 
