@@ -26,6 +26,11 @@ FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
 
 
+def flag_chunk_steps(row: int, col: int) -> int:
+    """VARLEN_ATTN_FLAG_CHUNK_STEPS(row, col): longest chunk of a row / column chain (0 = plan decides)."""
+    return ((int(row) & 0xFF) << 8) | ((int(col) & 0xFF) << 16)
+
+
 class Params(ctypes.Structure):
     _fields_ = [("total_tokens", ctypes.c_int32), ("num_docs", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),

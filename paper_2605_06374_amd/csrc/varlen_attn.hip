@@ -82,20 +82,6 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-// A operand = transpose of rows [row_base + 4h + {0..3}] and [row_base + 8 + 4h + {0..3}]
-// of a tile, columns 32 * dblk + c.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_read_trans_frag(const char* tile, int row_base, int dblk,
-                                                      int lane) {
-  const int i = lane & 15, b16 = (lane >> 4) & 1, h = lane >> 5;
-  const int row = row_base + 4 * h + (i >> 2);
-  const int chunk = 4 * dblk + 2 * b16 + ((i & 3) >> 1);
-  const int sub = (i & 1) * 8;
-  bf16x4 lo = lds_read_tr(tile + chunk_off<D>(row, chunk) + sub);
-  bf16x4 hi = lds_read_tr(tile + chunk_off<D>(row + 8, chunk) + sub);
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -130,34 +116,6 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
   bf16x2 b0 = __builtin_convertvector(t0, bf16x2), b1 = __builtin_convertvector(t1, bf16x2);
   return uint2{__builtin_bit_cast(unsigned, b0), __builtin_bit_cast(unsigned, b1)};
 }
-
-// Stage `ROWS` rows x D columns (row stride `stride` elements) into registers, zero beyond
-// `row_limit`; then write them, swizzled, into an LDS tile.
-template <int D, int ROWS>
-struct TileStager {
-  static constexpr int kChunks = ROWS * (D / 8) / kThreads;
-  uint4 reg[kChunks];
-  __device__ __forceinline__ void load(const __bf16* base, size_t stride, int row0, int row_limit,
-                                       int tid) {
-#pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int id = tid + i * kThreads;
-      const int row = id / (D / 8), c = id % (D / 8);
-      const int grow = row0 + row;
-      reg[i] = uint4{0, 0, 0, 0};
-      if (grow < row_limit)
-        reg[i] = *reinterpret_cast<const uint4*>(base + (size_t)grow * stride + c * 8);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int id = tid + i * kThreads;
-      const int row = id / (D / 8), c = id % (D / 8);
-      *reinterpret_cast<uint4*>(tile + chunk_off<D>(row, c)) = reg[i];
-    }
-  }
-};
 
 // ----------------------------------------------------------------------------------------
 // Global -> LDS staging without registers (global_load_lds_dwordx4): the 64 lanes of a wave

@@ -312,6 +312,21 @@ def test_no_split_mode_parity(gpu):
         assert_close_full(prob.results(), oracle_full(w), "no_split " + w.name)
 
 
+def test_caller_given_chunk_lengths(gpu):
+    """Chunk lengths passed through the flag bits: the plan uses them (or longer ones when the
+    partials would not fit), stays a valid partition, and the results still match the oracle."""
+    from paper_2605_06374_amd import binding
+    w = W.custom("forced_chunks", [1500, 130, 700], 2, 1, 128, seed=33)
+    flags = binding.flag_chunk_steps(3, 5)
+    prob = run_all(gpu, w, flags=flags)
+    plan = _check_plan(prob, w, False)
+    hdr = plan["header"]
+    assert hdr.row_chunk_steps >= 3 and hdr.col_chunk_steps >= 5
+    assert int(plan["row_units"][:, 6].max()) <= hdr.row_chunk_steps
+    assert int(plan["col_units"][:, 6].max()) <= hdr.col_chunk_steps
+    assert_close_full(prob.results(), oracle_full(w), "forced chunks")
+
+
 def test_bit_reproducible(gpu):
     w = W.config(4)
     a = run_all(gpu, w).result_bits()
