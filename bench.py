@@ -236,7 +236,19 @@ def sweep(args) -> int:
         stop.synchronize()
         if r >= 5:
             tt.append(start.elapsed_time(stop) * 1e3)
-    print(json.dumps({"sweep": "cfg5", "microbatches": 64, "fit_us": {"c0": round(float(c0), 2),
+    # Eq. 1 through the predictor library: fitted on the even micro-batches, judged on the odd
+    from paper_2605_06374_amd import mb_time as MB
+    n_tok = np.array([4096] * 64, dtype=np.int64)
+    ssq = np.array([r[2] for r in rows], dtype=np.int64)
+    model = MB.mb_time_fit(n_tok[0::2], ssq[0::2], t_us[0::2])
+    held_pred = np.array([MB.mb_time_predict(model, int(n), int(q)) for n, q in zip(n_tok[1::2], ssq[1::2])])
+    held_obs = t_us[1::2]
+    eq1 = {"alpha_us_per_token": model.alpha, "beta_us_per_squared_length": model.beta,
+           "fitted_on": 32, "held_out": 32,
+           "held_out_mape_percent": round(MB.mb_time_mape_percent(model, n_tok[1::2], ssq[1::2], held_obs), 2),
+           "false_alarms_at_25_percent": int(sum(MB.mb_time_is_suspicious(o, p) for o, p in zip(held_obs, held_pred))),
+           "flagged_when_slowed_1.5x": int(sum(MB.mb_time_is_suspicious(1.5 * o, p) for o, p in zip(held_obs, held_pred)))}
+    print(json.dumps({"sweep": "cfg5", "microbatches": 64, "eq1_model": eq1, "fit_us": {"c0": round(float(c0), 2),
                       "beta_per_pair": float(beta)}, "r2": round(r2, 4), "mape_percent": round(mape, 2),
                       "one_4096_doc_us": round(one4k, 1), "four_1024_docs_us": round(float(np.median(tt)), 1),
                       "time_ratio_4k_vs_4x1k": round(one4k / float(np.median(tt)), 2),

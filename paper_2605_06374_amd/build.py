@@ -1,4 +1,5 @@
-"""Compile csrc/varlen_attn.hip for gfx950 into libvarlen_attn.so next to this file."""
+"""Compile csrc/varlen_attn.hip for gfx950 into libvarlen_attn.so, and the host-only
+csrc/mb_time.cpp into libmb_time.so, next to this file."""
 from __future__ import annotations
 
 import os
@@ -23,7 +24,21 @@ FLAGS = [
 ]
 
 
+HOST_SRC = os.path.join(HERE, "csrc", "mb_time.cpp")
+HOST_LIB = os.path.join(HERE, "libmb_time.so")
+
+
+def build_host(verbose: bool = False) -> str:
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
+           "-I" + os.path.join(ROOT, "include"), "-o", HOST_LIB, HOST_SRC]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return HOST_LIB
+
+
 def build(verbose: bool = False) -> str:
+    build_host(verbose)
     cmd = [HIPCC] + FLAGS + ["-o", LIB, SRC]
     if verbose:
         print(" ".join(cmd))
