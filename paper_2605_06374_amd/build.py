@@ -1,5 +1,6 @@
 """Compile csrc/varlen_attn.hip for gfx950 into libvarlen_attn.so, and the host-only
-csrc/mb_time.cpp into libmb_time.so, next to this file."""
+csrc/mb_time.cpp and csrc/pipeline_dag.cpp into libmb_time.so and libpipeline_dag.so, next to
+this file."""
 from __future__ import annotations
 
 import os
@@ -24,17 +25,21 @@ FLAGS = [
 ]
 
 
-HOST_SRC = os.path.join(HERE, "csrc", "mb_time.cpp")
-HOST_LIB = os.path.join(HERE, "libmb_time.so")
+# host-only libraries: the Detector's predictors of Section 5.2
+HOST_LIBS = {"libmb_time.so": "mb_time.cpp", "libpipeline_dag.so": "pipeline_dag.cpp"}
 
 
-def build_host(verbose: bool = False) -> str:
-    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-I" + os.path.join(ROOT, "include"), "-o", HOST_LIB, HOST_SRC]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
-    return HOST_LIB
+def build_host(verbose: bool = False) -> list:
+    out = []
+    for lib, src in HOST_LIBS.items():
+        cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-I" + os.path.join(ROOT, "include"), "-o", os.path.join(HERE, lib),
+               os.path.join(HERE, "csrc", src)]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
+        out.append(os.path.join(HERE, lib))
+    return out
 
 
 def build(verbose: bool = False) -> str:
