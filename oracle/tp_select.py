@@ -1,4 +1,4 @@
-"""Oracle (test infrastructure, CPU): selective device exclusion inside a TP group, Section 4.1.
+"""Oracle (test infrastructure, CPU): selective device exclusion inside a TP group, Section 6.1.
 
 G is the original TP group, F_stop its fail-stop devices, G' = G \\ F_stop.  Feasible degrees
 (Eq. 3): K = {k : k_min <= k <= |G'|, k a power of two}.  For each k the candidate S_k is the

@@ -1,4 +1,4 @@
-"""Pins of the TP subgroup selection oracle (Section 4.1, Eq. 3 and Eq. 4)."""
+"""Pins of the TP subgroup selection oracle (Section 6.1, Eq. 3 and Eq. 4)."""
 import itertools
 
 import numpy as np
