@@ -46,6 +46,9 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy 4 times, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step per buffer set in a HIP graph and time the replays "
+                         "(`graph_ms_per_step` in the JSON line)")
     ap.add_argument("--mfma-rate", action="store_true",
                     help="also time a pure bf16 MFMA kernel with constant and with hashed operands "
                          "(what the matrix pipe sustains on this box) and report both")
@@ -127,6 +130,26 @@ def main() -> int:
                     "algorithmic_flops_per_launch": alg,
                     "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graphs = []
+        for p in probs:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                p.forward()
+                p.backward(reuse_plan=True)
+            graphs.append(g)
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) / args.steps * 1e3
+
     mfma_rate = None
     if args.mfma_rate:
         scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
@@ -184,6 +207,8 @@ def main() -> int:
     }
     if mfma_rate:
         out["mfma_rate"] = mfma_rate
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = round(graph_ms, 5)
     print(json.dumps(out))
     return 0
 

@@ -355,6 +355,48 @@ def test_cost_follows_sum_of_squares_not_n_squared(gpu):
     assert 3.5 < a / b < 4.0
 
 
+def test_hip_graph_replays_match_eager(gpu):
+    """fwd + bwd enqueue kernels only (no allocation, no synchronisation, no memset nodes), so
+    a caller may capture them in a HIP graph: every replay, with eager work and
+    synchronisations between the replays, reproduces the eager results bit for bit."""
+    import torch
+    w = W.custom("graph", [700, 64, 1, 900, 333], 4, 2, 128, seed=77)
+    eager = run_all(gpu, w)
+    want = eager.result_bits()
+    prob = gpu.DeviceProblem(w)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):        # warm-up on the capture stream
+        prob.forward()
+        prob.backward(reuse_plan=True)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        prob.forward()
+        prob.backward(reuse_plan=True)
+    for replay in range(3):
+        prob.poison_outputs()
+        prob.workspace.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = prob.result_bits()
+        for n in want:
+            assert np.array_equal(got[n], want[n]), (replay, n)
+        other = run_all(gpu, W.config(1))      # eager work between the replays
+        torch.cuda.synchronize()
+        del other
+
+
+def test_long_single_document_sampled(gpu):
+    """131072 tokens in one document (1024 tiles, chains of up to 2048 steps, cut into
+    chunks): sampled rows and keys against the oracle plus the size-independent properties."""
+    w = W.custom("long131k", [131072], 2, 1, 128, seed=5)
+    prob = _sampled_parity(gpu, w, n_rows=24, n_keys=24, seed=131)
+    assert prob.read_plan()["header"].pairs == w.pairs == 131072 * 131073 // 2
+
+
 def test_mfma_rate_probe_runs(gpu):
     """The measurement aid returns a plausible rate and rejects bad arguments."""
     import torch
