@@ -1,6 +1,6 @@
 """Compile csrc/varlen_attn.hip for gfx950 into libvarlen_attn.so, and the host-only
-csrc/mb_time.cpp, csrc/pipeline_dag.cpp and csrc/tp_select.cpp into libmb_time.so,
-libpipeline_dag.so and libtp_select.so, next to this file."""
+csrc/mb_time.cpp, csrc/pipeline_dag.cpp, csrc/tp_select.cpp and csrc/migration_step.cpp into
+shared libraries of the same names, next to this file."""
 from __future__ import annotations
 
 import os
@@ -26,9 +26,9 @@ FLAGS = [
 
 
 # host-only libraries: the Detector's predictors of Section 5.2, the Scheduler's TP subgroup
-# selection of Section 6.1
+# selection of Section 6.1 and migration decision of Section 6.3
 HOST_LIBS = {"libmb_time.so": "mb_time.cpp", "libpipeline_dag.so": "pipeline_dag.cpp",
-             "libtp_select.so": "tp_select.cpp"}
+             "libtp_select.so": "tp_select.cpp", "libmigration_step.so": "migration_step.cpp"}
 
 
 def build_host(verbose: bool = False) -> list:
