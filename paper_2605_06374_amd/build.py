@@ -1,4 +1,4 @@
-"""Compile csrc/varlen_attn.hip for gfx950 into libvarlen_attn.so, and the host-only
+"""Compile csrc/varlen_attn.hip (with the .hpp files it includes) for gfx950 into libvarlen_attn.so, and the host-only
 csrc/mb_time.cpp, csrc/pipeline_dag.cpp, csrc/tp_select.cpp and csrc/migration_step.cpp into
 shared libraries of the same names, next to this file."""
 from __future__ import annotations

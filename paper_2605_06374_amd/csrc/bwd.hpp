@@ -1,0 +1,476 @@
+// Backward kernels (dQ; dK and dV) and the reduction of their partial results.
+#ifndef VARLEN_ATTN_BWD_HPP_
+#define VARLEN_ATTN_BWD_HPP_
+
+#include "tiles.hpp"
+#include "staging.hpp"
+#include "fragments.hpp"
+
+namespace {
+
+// ----------------------------------------------------------------------------------------
+// Backward, dQ (first backward kernel).  Same decomposition as the forward: one workgroup per
+// (row unit, q head).  Its prologue also computes D = rowsum(dO * O) for its rows.
+// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T (dP^T - D), dQ^T += K^T dS^T.
+// ----------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(kThreads, 2)
+bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+              const __bf16* __restrict__ v, const __bf16* __restrict__ o,
+              const __bf16* __restrict__ d_o, const float* __restrict__ lse,
+              float* __restrict__ dsum, float* __restrict__ lse2_out,
+              const varlen_attn_plan_header* __restrict__ hdr,
+              const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dq,
+              float* __restrict__ partials, int N, int Hq, int Hkv, float scale,
+              int max_units) {
+  constexpr int KK = D / 16, DB = D / 32;
+  constexpr int NS = 4;
+  constexpr int kStageBytes = kSub * D * 2;
+  constexpr int LPS = 2 * StageLoader<D>::kPerWave;
+  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes];  // K stages, V stages
+
+  int unit_idx, head;
+  decode_block(blockIdx.x, Hq, unit_idx, head);
+  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+  const int n_units = hdr->n_row_units;
+  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  if (unit_idx >= n_units) return;
+  const int kvh = head / (Hq / Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
+  const float cs = scale * kLog2e;
+
+  const int wave_row0 = it.row0 + 32 * wave;
+  const int my_row = wave_row0 + c;
+  const bool row_valid = my_row < it.doc_end;
+  const bool wave_active = wave_row0 < it.doc_end;
+  const int wave_last_row = min(wave_row0 + 31, it.doc_end - 1);
+  const int wg_last_row = min(it.row0 + kTile, it.doc_end) - 1;
+  const int kv_begin = it.doc_start + it.step_begin * kStep;
+  const int kv_end = min(it.doc_start + it.step_end * kStep, wg_last_row + 1);
+  const int n_sub = (kv_end - kv_begin + kSub - 1) / kSub;
+
+  const __bf16* kbase = k + (size_t)kvh * D;
+  const __bf16* vbase = v + (size_t)kvh * D;
+  const unsigned lds_k = lds_addr_of(smem), lds_v = lds_k + NS * kStageBytes;
+
+  StageLoader<D> loader;
+  loader.init(wave, lane, (unsigned)((size_t)Hkv * D * 2));
+  auto issue = [&](int sub, int stage) {
+    const int row0 = kv_begin + kSub * min(sub, n_sub - 1);
+    loader.issue(kbase, row0, it.doc_end - 1, lds_k + stage * kStageBytes, wave);
+    loader.issue(vbase, row0, it.doc_end - 1, lds_v + stage * kStageBytes, wave);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st, st);
+
+  // Q and dO fragments stay in registers; the O fragments are only needed for
+  // D = rowsum(dO * O): each lane holds half of its row's columns, the other half-wave the rest.
+  bf16x8 qf[KK], dof[KK];
+  float d_part = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    uint4 t = {0, 0, 0, 0}, u = {0, 0, 0, 0}, w = {0, 0, 0, 0};
+    if (row_valid) {
+      const size_t off = ((size_t)my_row * Hq + head) * D + 16 * kk + 8 * h;
+      t = *reinterpret_cast<const uint4*>(q + off);
+      u = *reinterpret_cast<const uint4*>(d_o + off);
+      w = *reinterpret_cast<const uint4*>(o + off);
+    }
+    qf[kk] = __builtin_bit_cast(bf16x8, t);
+    dof[kk] = __builtin_bit_cast(bf16x8, u);
+    const bf16x8 of = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d_part += (float)dof[kk][e] * (float)of[e];
+  }
+  const float dsum_row = half_sum(d_part);
+  // rows past the document end get LSE = +huge so that their P is exactly 0
+  const float lse2 = row_valid ? lse[(size_t)head * N + my_row] * kLog2e : 1e30f;
+  // the unit that starts the chain publishes D and LSE * log2(e) for the dK/dV kernel
+  if (it.step_begin == 0 && row_valid && h == 0) {
+    dsum[(size_t)head * N + my_row] = dsum_row;
+    lse2_out[(size_t)head * N + my_row] = lse2;
+  }
+  FragOffsets<D> fo;
+  fo.init(lane);
+  wait_all_vm_visible();
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int i = 0; i < DB; ++i) acc[i] = f32x16(0.f);
+
+  auto compute = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    const int kv0 = kv_begin + kSub * sub;
+    if (!(wave_active && kv0 <= wave_last_row)) return;
+    const char* kt = smem + ST * kStageBytes;
+    const char* vt = smem + (NS + ST) * kStageBytes;
+    f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
+      dp = mfma(lds_read_frag(vt, fo.row_frag[kk]), dof[kk], dp);
+    }
+    const bool diag = kv0 + kSub - 1 > wave_row0;
+    const int t = my_row - kv0 - 4 * h;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
+      if (diag && 8 * (r / 4) + (r % 4) > t) p = 0.f;
+      s[r] = p * (dp[r] - dsum_row);
+    }
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const bf16x8 dsb = pack8(s, 8 * cc);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) acc[db] = mfma(read_trans<D>(kt, fo, cc, db), dsb, acc[db]);
+    }
+  };
+  auto body = [&](int sub, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    wait_vm<(NS - 2) * LPS>();
+    __syncthreads();
+    issue(sub + NS - 1, (ST + NS - 1) % NS);
+    compute(sub, stage_c);
+  };
+  for (int sub = 0; sub < n_sub; sub += NS) {
+    body(sub, std::integral_constant<int, 0>{});
+    if (sub + 1 >= n_sub) break;
+    body(sub + 1, std::integral_constant<int, 1>{});
+    if (sub + 2 >= n_sub) break;
+    body(sub + 2, std::integral_constant<int, 2>{});
+    if (sub + 3 >= n_sub) break;
+    body(sub + 3, std::integral_constant<int, 3>{});
+  }
+  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
+
+  if (it.slot >= 0) {
+    store_frag<D>(partials + ((size_t)it.slot * Hq + head) * frag_floats<D>(), acc, wave, lane);
+    return;
+  }
+  if (row_valid) store_rows<D>(dq + ((size_t)my_row * Hq + head) * D, acc, h, scale);
+}
+
+// ----------------------------------------------------------------------------------------
+// Backward, dK and dV.  One workgroup per (column unit, q head): wave w owns key rows
+// row0 + 32w .. +31, keeps their K and V fragments in registers, and sweeps the unit's
+// query steps (from the diagonal towards the document end).
+//   S = Q K^T, dP = dO V^T (query rows in registers r, key on the lane),
+//   dV^T += dO^T P,  dK^T += Q^T dS.
+// With grouped-query attention, or when the chain is cut, the unit stores fp32 partials
+// [dK | dV] that sum_combine_kernel adds up over the chunks and the q heads of the group.
+// ----------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(kThreads, 1)
+bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+               const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
+               const float* __restrict__ lse2, const float* __restrict__ dsum,
+               const varlen_attn_plan_header* __restrict__ hdr,
+               const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dk,
+               __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
+               float scale, int max_units) {
+  constexpr int KK = D / 16, DB = D / 32;
+  // Two stages of kStep = 64 query rows: one stage of lookahead is a whole stage of compute
+  // (this kernel runs one workgroup per CU), and 64 KB of tiles keeps every LDS offset inside
+  // the 16-bit immediate of the read instructions.
+  constexpr int NS = 2;
+  constexpr int kStageBytes = kStep * D * 2;
+  constexpr int kStatBytes = 512;             // lse2[64] then dsum[64], one copy per wave
+  using Loader = StageLoader<D, kStep>;
+  constexpr int LPS = 2 * Loader::kPerWave + 2;
+  // Q stages | dO stages | per-wave stat copies
+  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes + NS * 4 * kStatBytes];
+
+  int unit_idx, head;
+  decode_block(blockIdx.x, Hq, unit_idx, head);
+  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+  const int n_units = hdr->n_col_units;
+  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  if (unit_idx >= n_units) return;
+  const int kvh = head / (Hq / Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
+  const float cs = scale * kLog2e;
+
+  const int wave_kv0 = it.row0 + 32 * wave;
+  const int my_kv = wave_kv0 + c;
+  const bool kv_valid = my_kv < it.doc_end;
+  const bool wave_active = wave_kv0 < it.doc_end;
+  const int n_steps = it.step_end - it.step_begin;
+
+  const __bf16* qbase = q + (size_t)head * D;
+  const __bf16* dobase = d_o + (size_t)head * D;
+  const float* lse_h = lse2 + (size_t)head * N;
+  const float* dsum_h = dsum + (size_t)head * N;
+  const unsigned lds_q = lds_addr_of(smem), lds_do = lds_q + NS * kStageBytes;
+  const unsigned lds_stat = lds_do + NS * kStageBytes + wave * kStatBytes;
+  const char* stat_base = smem + 2 * NS * kStageBytes + wave * kStatBytes;
+
+  Loader loader;
+  loader.init(wave, lane, (unsigned)((size_t)Hq * D * 2));
+  auto issue = [&](int st, int stage) {
+    const int q0 = it.row0 + kStep * (it.step_begin + min(st, n_steps - 1));
+    loader.issue(qbase, q0, it.doc_end - 1, lds_q + stage * kStageBytes, wave);
+    loader.issue(dobase, q0, it.doc_end - 1, lds_do + stage * kStageBytes, wave);
+    dma_floats64(lse_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes, lane);
+    dma_floats64(dsum_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes + 256, lane);
+  };
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st) issue(st, st);
+
+  bf16x8 kf[KK], vf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    uint4 t = {0, 0, 0, 0}, u = {0, 0, 0, 0};
+    if (kv_valid) {
+      const size_t off = ((size_t)my_kv * Hkv + kvh) * D + 16 * kk + 8 * h;
+      t = *reinterpret_cast<const uint4*>(k + off);
+      u = *reinterpret_cast<const uint4*>(v + off);
+    }
+    kf[kk] = __builtin_bit_cast(bf16x8, t);
+    vf[kk] = __builtin_bit_cast(bf16x8, u);
+  }
+  FragOffsets<D> fo;
+  fo.init(lane);
+  wait_all_vm_visible();
+
+  f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+  for (int i = 0; i < DB; ++i) { dkacc[i] = f32x16(0.f); dvacc[i] = f32x16(0.f); }
+
+  // One 32-query block of a stage against this wave's 32 keys.  MASKED: the block may touch
+  // the diagonal or run past the document end (queries there are clamped duplicates).
+  auto block = [&](const char* qt, const char* dot, const char* st, int qb, int q0, auto masked_c) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    const int qb0 = q0 + 32 * qb;
+    if (MASKED && (qb0 + 31 < wave_kv0 || qb0 >= it.doc_end)) return;  // wave-uniform
+    f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      s = mfma(lds_read_frag(qt, fo.row_frag[kk] + qb * 32 * D * 2), kf[kk], s);
+      dp = mfma(lds_read_frag(dot, fo.row_frag[kk] + qb * 32 * D * 2), vf[kk], dp);
+    }
+    f32x16 p;
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int rel = 32 * qb + 8 * rq + 4 * h;
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + rel * 4);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + rel * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * rq + e;
+        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -l4[e]));
+        if (MASKED) {
+          const int t = q0 + rel + e;
+          if (t < my_kv || t >= it.doc_end) pv = 0.f;
+        }
+        p[r] = pv;
+        s[r] = pv * (dp[r] - d4[e]);
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const bf16x8 pb = pack8(p, 8 * cc);
+      const bf16x8 dsb = pack8(s, 8 * cc);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma(read_trans<D>(dot + qb * 32 * D * 2, fo, cc, db), pb, dvacc[db]);
+        dkacc[db] = mfma(read_trans<D>(qt + qb * 32 * D * 2, fo, cc, db), dsb, dkacc[db]);
+      }
+    }
+  };
+  // A whole 64-query stage away from the diagonal and the document end: the two 32-query
+  // blocks are software-pipelined by hand (this kernel runs one wave per SIMD, so nothing
+  // else hides LDS latency or overlaps the exponentials with the matrix pipe):
+  //   R0 | M1(0) + R1 | V(0) with M1(1) + T0 | M2(0) with V(1) + T1 | M2(1)
+  // R: row-fragment and statistics reads, T: transposed-fragment reads, M1: S and dP,
+  // V: P and dS on the vector ALU, M2: dV and dK.  Each matrix instruction is written next to
+  // the vector and LDS work that should ride on it, and the fences keep that order.
+  auto stage_fast = [&](const char* qt, const char* dot, const char* st) {
+    constexpr int EPM = 16 / (2 * KK);  // score elements handled beside each matrix instruction
+    bf16x8 qa[KK], da[KK], qb[KK], db_[KK];
+    bf16x8 tq0[2][DB], td0[2][DB], tq1[2][DB], td1[2][DB];
+    f32x4 l0[4], d0[4], l1[4], d1[4];
+    // softmax of element r of one block: p = 2^(s cs - lse2), ds = p (dp - D)
+    auto soft = [&](f32x16& sv, const f32x16& dpv, f32x16& pv, const f32x4* l, const f32x4* dd, int r) {
+      const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], cs, -l[r >> 2][r & 3]));
+      pv[r] = e;
+      sv[r] = e * (dpv[r] - dd[r >> 2][r & 3]);
+    };
+    // ---- R0
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qa[kk] = lds_read_frag(qt, fo.row_frag[kk]);
+      da[kk] = lds_read_frag(dot, fo.row_frag[kk]);
+    }
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      l0[rq] = *reinterpret_cast<const f32x4*>(st + (8 * rq + 4 * h) * 4);
+      d0[rq] = *reinterpret_cast<const f32x4*>(st + 256 + (8 * rq + 4 * h) * 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- M1(0) + R1
+    f32x16 s0 = f32x16(0.f), dp0 = f32x16(0.f);
+    static_for<KK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      s0 = mfma(qa[kk], kf[kk], s0);
+      qb[kk] = lds_read_frag(qt, fo.row_frag[kk] + 32 * D * 2);
+      if (kk < 4) l1[kk] = *reinterpret_cast<const f32x4*>(st + (32 + 8 * kk + 4 * h) * 4);
+      __builtin_amdgcn_sched_barrier(0);
+      dp0 = mfma(da[kk], vf[kk], dp0);
+      db_[kk] = lds_read_frag(dot, fo.row_frag[kk] + 32 * D * 2);
+      if (kk < 4) d1[kk] = *reinterpret_cast<const f32x4*>(st + 256 + (32 + 8 * kk + 4 * h) * 4);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- V(0) with M1(1) + T0
+    f32x16 p0, s1 = f32x16(0.f), dp1 = f32x16(0.f);
+    bf16x8 pb0[2], dsb0[2];
+    static_for<KK>([&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      s1 = mfma(qb[kk], kf[kk], s1);
+#pragma unroll
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * 2 * kk + e);
+      td0[kk / DB][kk % DB] = read_trans<D>(dot, fo, kk / DB, kk % DB);
+      __builtin_amdgcn_sched_barrier(0);
+      dp1 = mfma(db_[kk], vf[kk], dp1);
+#pragma unroll
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * (2 * kk + 1) + e);
+      tq0[kk / DB][kk % DB] = read_trans<D>(qt, fo, kk / DB, kk % DB);
+      if ((kk + 1) * 2 * EPM % 8 == 0) {
+        constexpr int i = (kk + 1) * 2 * EPM / 8 - 1;
+        pb0[i] = pack8(p0, 8 * i);
+        dsb0[i] = pack8(s0, 8 * i);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- M2(0) with V(1) + T1
+    f32x16 p1;
+    bf16x8 pb1[2], dsb1[2];
+    static_for<2 * DB>([&](auto j_c) {
+      constexpr int j = decltype(j_c)::value;
+      dvacc[j % DB] = mfma(td0[j / DB][j % DB], pb0[j / DB], dvacc[j % DB]);
+#pragma unroll
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * 2 * j + e);
+      td1[j / DB][j % DB] = read_trans<D>(dot + 32 * D * 2, fo, j / DB, j % DB);
+      __builtin_amdgcn_sched_barrier(0);
+      dkacc[j % DB] = mfma(tq0[j / DB][j % DB], dsb0[j / DB], dkacc[j % DB]);
+#pragma unroll
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * (2 * j + 1) + e);
+      tq1[j / DB][j % DB] = read_trans<D>(qt + 32 * D * 2, fo, j / DB, j % DB);
+      if ((j + 1) * 2 * EPM % 8 == 0) {
+        constexpr int i = (j + 1) * 2 * EPM / 8 - 1;
+        pb1[i] = pack8(p1, 8 * i);
+        dsb1[i] = pack8(s1, 8 * i);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- M2(1)
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dvacc[db] = mfma(td1[cc][db], pb1[cc], dvacc[db]);
+        dkacc[db] = mfma(tq1[cc][db], dsb1[cc], dkacc[db]);
+      }
+  };
+  auto body = [&](int st, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    wait_vm<(NS - 2) * LPS>();
+    __syncthreads();
+    issue(st + NS - 1, (ST + NS - 1) % NS);
+    if (!wave_active) return;
+    const int step = it.step_begin + st;
+    const int q0 = it.row0 + kStep * step;
+    const char* qt = smem + ST * kStageBytes;
+    const char* dot = smem + (NS + ST) * kStageBytes;
+    const char* stt = stat_base + ST * 4 * kStatBytes;
+    if (step < 2 || q0 + kStep > it.doc_end) {
+      block(qt, dot, stt, 0, q0, std::true_type{});
+      block(qt, dot, stt, 1, q0, std::true_type{});
+    } else {
+      stage_fast(qt, dot, stt);
+    }
+  };
+  for (int st = 0; st < n_steps; st += NS) {
+    body(st, std::integral_constant<int, 0>{});
+    if (st + 1 >= n_steps) break;
+    body(st + 1, std::integral_constant<int, 1>{});
+  }
+  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
+
+  if (it.slot >= 0) {
+    float* part = partials + ((size_t)it.slot * Hq + head) * 2 * frag_floats<D>();
+    store_frag<D>(part, dkacc, wave, lane);
+    store_frag<D>(part + frag_floats<D>(), dvacc, wave, lane);
+    return;
+  }
+  if (kv_valid) {
+    store_rows<D>(dk + ((size_t)my_kv * Hkv + kvh) * D, dkacc, h, scale);
+    store_rows<D>(dv + ((size_t)my_kv * Hkv + kvh) * D, dvacc, h, 1.0f);
+  }
+}
+
+// Adds up fp32 partial fragments in a fixed order (chunks in chain order, then the q heads of
+// the group) and stores bf16 rows.  NT tensors per partial (dQ: 1; [dK | dV]: 2), G partial
+// heads per output head; tensor 0 is multiplied by `scale0`.  Elementwise: thread t owns
+// float4 number t of the fragment.
+template <int D, int NT>
+__device__ __forceinline__ void sum_combine(int block, int n_items,
+                                            const varlen_attn_combine_item* __restrict__ items,
+                                            const float* __restrict__ partials,
+                                            __bf16* __restrict__ out0, __bf16* __restrict__ out1,
+                                            int Hin, int G, float scale0) {
+  constexpr int DB = D / 32;
+  constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
+  const int Hout = Hin / G;
+  const int sub = block % kBlocksPerItem;
+  int rest = block / kBlocksPerItem;
+  const int tensor = rest % NT; rest /= NT;
+  const int idx = rest / Hout, oh = rest % Hout;
+  if (idx >= n_items) return;
+  const varlen_attn_combine_item it = items[idx];
+  const int t = sub * kThreads + threadIdx.x;
+  const int lane = t & 63, rq = (t >> 6) & 3, db = (t >> 8) % DB, wave = (t >> 8) / DB;
+  const int h = lane >> 5, c = lane & 31;
+  const int my_row = it.row0 + 32 * wave + c;
+  if (my_row >= it.doc_end) return;
+  const size_t psize = NT * frag_floats<D>();
+  const float* p0 = partials + ((size_t)it.slot0 * Hin + oh * G) * psize + tensor * frag_floats<D>() +
+                    (size_t)t * 4;
+  // partial number j = ch * G + gh sits (ch * Hin + gh) partial sizes after the first; four
+  // loads are kept in flight, the additions stay in index order (deterministic)
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const int n_parts = it.n_chunks * G;
+  auto part = [&](int j) {
+    return *reinterpret_cast<const f32x4*>(p0 + ((size_t)(j / G) * Hin + (j % G)) * psize);
+  };
+  int j = 0;
+  for (; j + 4 <= n_parts; j += 4) {
+    const f32x4 x0 = part(j), x1 = part(j + 1), x2 = part(j + 2), x3 = part(j + 3);
+    acc += x0; acc += x1; acc += x2; acc += x3;
+  }
+  for (; j < n_parts; ++j) acc += part(j);
+  const float mul = tensor == 0 ? scale0 : 1.0f;
+  __bf16* out = tensor == 0 ? out0 : out1;
+  *reinterpret_cast<uint2*>(out + ((size_t)my_row * Hout + oh) * D + 32 * db + 8 * rq + 4 * h) =
+      pack4(acc[0] * mul, acc[1] * mul, acc[2] * mul, acc[3] * mul);
+}
+
+// One launch for both backward reductions: the first `dkv_blocks` workgroups sum the
+// [dK | dV] partials (over chunks and the q heads of a group), the rest sum the dQ partials.
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
+                   const varlen_attn_combine_item* __restrict__ col_items,
+                   const varlen_attn_combine_item* __restrict__ row_items,
+                   const float* __restrict__ col_partials, const float* __restrict__ row_partials,
+                   __bf16* __restrict__ dk, __bf16* __restrict__ dv, __bf16* __restrict__ dq,
+                   int Hq, int Hkv, float scale, int dkv_blocks) {
+  if ((int)blockIdx.x < dkv_blocks)
+    sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale);
+  else
+    sum_combine<D, 1>(blockIdx.x - dkv_blocks, hdr->n_row_combine, row_items, row_partials, dq, nullptr,
+                      Hq, 1, scale);
+}
+
+}  // namespace
+
+#endif  // VARLEN_ATTN_BWD_HPP_
