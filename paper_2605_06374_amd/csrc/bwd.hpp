@@ -110,19 +110,35 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
       dp = mfma(lds_read_frag(vt, fo.row_frag[kk]), dof[kk], dp);
     }
-    const bool diag = kv0 + kSub - 1 > wave_row0;
-    const int t = my_row - kv0 - 4 * h;
+    // the transposed K fragments of the last contraction are requested before the vector
+    // work, so that they arrive behind it
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 ktf[2][DB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
-      if (diag && 8 * (r / 4) + (r % 4) > t) p = 0.f;
-      s[r] = p * (dp[r] - dsum_row);
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) ktf[cc][db] = read_trans<D>(kt, fo, cc, db);
+    __builtin_amdgcn_sched_barrier(0);
+    if (kv0 + kSub - 1 > wave_row0) {  // touches the diagonal for some row (wave-uniform)
+      const int t = my_row - kv0 - 4 * h;  // key offset 8 (r / 4) + r % 4 is allowed iff <= t
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
+        if (8 * (r / 4) + (r % 4) > t) p = 0.f;
+        s[r] = p * (dp[r] - dsum_row);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -lse2));
+        s[r] = p * (dp[r] - dsum_row);
+      }
     }
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const bf16x8 dsb = pack8(s, 8 * cc);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) acc[db] = mfma(read_trans<D>(kt, fo, cc, db), dsb, acc[db]);
+      for (int db = 0; db < DB; ++db) acc[db] = mfma(ktf[cc][db], dsb, acc[db]);
     }
   };
   auto body = [&](int sub, auto stage_c) {
