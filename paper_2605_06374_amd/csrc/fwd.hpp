@@ -92,6 +92,15 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     f32x16 s = f32x16(0.f);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
+    // the transposed V fragments of the second contraction are requested before the softmax
+    // arithmetic, so that they arrive behind it
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 vtf[2][DB];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vtf[cc][db] = read_trans<D>(vt, fo, cc, db);
+    __builtin_amdgcn_sched_barrier(0);
     if (kv0 + kSub - 1 > wave_row0) {  // touches the diagonal for some row
       const int t = my_row - kv0 - 4 * h;  // key offset 8 (r / 4) + r % 4 is allowed iff <= t
 #pragma unroll
@@ -124,7 +133,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     for (int cc = 0; cc < 2; ++cc) {
       const bf16x8 pb = pack8(s, 8 * cc);
 #pragma unroll
-      for (int db = 0; db < DB; ++db) oacc[db] = mfma(read_trans<D>(vt, fo, cc, db), pb, oacc[db]);
+      for (int db = 0; db < DB; ++db) oacc[db] = mfma(vtf[cc][db], pb, oacc[db]);
     }
   };
   // iteration `sub`: its stage has landed once at most NS-2 newer stages are in flight; the
