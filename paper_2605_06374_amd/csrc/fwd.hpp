@@ -55,10 +55,16 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
 
   StageLoader<D> loader;
   loader.init(wave, lane, (unsigned)(kv_stride * 2));
+  // stages are issued in order, one call per sub-step: the wave-uniform addresses of the next
+  // stage's first K and V rows live in scalar registers and move on by one stage per call
+  const unsigned long long kStageStride = (unsigned long long)kSub * (kv_stride * 2);
+  unsigned long long k_next = uniform64(reinterpret_cast<const char*>(kbase) + (size_t)kv_begin * (kv_stride * 2));
+  unsigned long long v_next = uniform64(reinterpret_cast<const char*>(vbase) + (size_t)kv_begin * (kv_stride * 2));
   auto issue = [&](int sub, int stage) {
     const int row0 = kv_begin + kSub * min(sub, n_sub - 1);
-    loader.issue(kbase, row0, it.doc_end - 1, lds_k + stage * kStageBytes, wave);
-    loader.issue(vbase, row0, it.doc_end - 1, lds_v + stage * kStageBytes, wave);
+    loader.issue_at(k_next, row0, it.doc_end - 1, lds_k + stage * kStageBytes, wave);
+    loader.issue_at(v_next, row0, it.doc_end - 1, lds_v + stage * kStageBytes, wave);
+    if (sub < n_sub - 1) { k_next += kStageStride; v_next += kStageStride; }
   };
 #pragma unroll
   for (int st = 0; st < NS - 1; ++st) issue(st, st);

@@ -72,8 +72,13 @@ struct StageLoader {
   // tile rows [row0, row0 + ROWS) of `base` -> LDS at `lds`; rows above row_last are clamped
   __device__ __forceinline__ void issue(const __bf16* base, int row0, int row_last, unsigned lds,
                                         int wave) const {
-    const unsigned long long b =
-        uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes);
+    issue_at(uniform64(reinterpret_cast<const char*>(base) + (size_t)row0 * stride_bytes), row0,
+             row_last, lds, wave);
+  }
+  // the same with the wave-uniform address of row `row0` already at hand (a chain keeps it in
+  // scalar registers and moves it on by one stage per call)
+  __device__ __forceinline__ void issue_at(unsigned long long b, int row0, int row_last,
+                                           unsigned lds, int wave) const {
     if (row0 + ROWS - 1 <= row_last) {
 #pragma unroll
       for (int i = 0; i < kPerWave; ++i)
