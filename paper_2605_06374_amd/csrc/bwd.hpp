@@ -111,11 +111,13 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     const char* kt = smem + ST * kStageBytes;
     const char* vt = smem + (NS + ST) * kStageBytes;
     f32x16 s = f32x16(0.f), dp = f32x16(0.f);
+    __builtin_amdgcn_s_setprio(2);   // matrix phases win the issue slot over the other wave's vector work
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
       dp = mfma(lds_read_frag(vt, fo.row_frag[kk]), dof[kk], dp);
     }
+    __builtin_amdgcn_s_setprio(0);
     // the transposed K fragments of the last contraction are requested before the vector
     // work, so that they arrive behind it
     __builtin_amdgcn_sched_barrier(0);
@@ -140,12 +142,14 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         s[r] = p * (dp[r] - dsum_row);
       }
     }
+    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const bf16x8 dsb = pack8(s, 8 * cc);
 #pragma unroll
       for (int db = 0; db < DB; ++db) acc[db] = mfma(ktf[cc][db], dsb, acc[db]);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   auto body = [&](int sub, auto stage_c) {
     constexpr int ST = decltype(stage_c)::value;

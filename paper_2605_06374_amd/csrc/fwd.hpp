@@ -96,8 +96,10 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     const char* kt = smem + ST * kStageBytes;
     const char* vt = smem + (NS + ST) * kStageBytes;
     f32x16 s = f32x16(0.f);
+    __builtin_amdgcn_s_setprio(2);   // matrix phases win the issue slot over the other wave's softmax
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) s = mfma(lds_read_frag(kt, fo.row_frag[kk]), qf[kk], s);
+    __builtin_amdgcn_s_setprio(0);
     // the transposed V fragments of the second contraction are requested before the softmax
     // arithmetic, so that they arrive behind it
     __builtin_amdgcn_sched_barrier(0);
@@ -135,12 +137,14 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
       psum += p;
     }
     l_run += psum;
+    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
       const bf16x8 pb = pack8(s, 8 * cc);
 #pragma unroll
       for (int db = 0; db < DB; ++db) oacc[db] = mfma(vtf[cc][db], pb, oacc[db]);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   // iteration `sub`: its stage has landed once at most NS-2 newer stages are in flight; the
   // barrier also tells that every wave is done with the stage about to be refilled
