@@ -70,6 +70,19 @@ def test_non_default_scale_and_std(gpu):
     assert_close_full(prob.results(), oracle_full(w), "scale 0.21")
 
 
+@pytest.mark.parametrize("std,d", [(4.0, 128), (3.0, 64), (0.01, 128)])
+def test_extreme_logit_ranges(gpu, std, d):
+    """Values four times larger give logits with a standard deviation of 16 (nearly one-hot
+    rows, the running max rises by far more than the lazy-rescale margin many times over);
+    tiny values give nearly uniform rows.  Both across cut chains."""
+    w = W.custom("logits", [900, 130, 1500], 2, 1, d, std=std, seed=int(std * 100) + d)
+    prob = run_all(gpu, w)
+    got = prob.results()
+    for name in ("o", "lse", "dq", "dk", "dv"):
+        assert np.isfinite(got[name]).all(), name
+    assert_close_full(got, oracle_full(w), f"std {std}")
+
+
 def test_config1_tiny_full(gpu):
     w = W.config(1)
     prob = run_all(gpu, w)
