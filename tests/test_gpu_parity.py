@@ -51,6 +51,9 @@ SMALL = [
     ([257, 511, 769], 8, 1, 128),             # 8:1 GQA
     ([16, 17, 18, 19, 20] * 8, 4, 4, 128),
     ([1537], 2, 2, 64),
+    ([300, 129], 16, 2, 64),                  # more q heads than XCDs
+    ([700, 40], 6, 3, 128),                   # head count that neither divides nor is divided by 8
+    ([260], 32, 32, 64),
 ]
 
 
