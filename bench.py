@@ -51,7 +51,8 @@ def main() -> int:
                          "(`graph_ms_per_step` in the JSON line)")
     ap.add_argument("--mfma-rate", action="store_true",
                     help="also time a pure bf16 MFMA kernel with constant and with hashed operands "
-                         "(what the matrix pipe sustains on this box) and report both")
+                         "(what the matrix pipe sustains on this box) and the LDS fragment reads "
+                         "of the kernels alone; reported under mfma_rate")
     ap.add_argument("--sweep", action="store_true",
                     help="length-skew sweep: time each of the 64 microbatches of configuration 5 "
                          "alone and fit T = c0 + beta * sum l(l+1)/2 (Eq. 1 at fixed N); prints a "
@@ -155,7 +156,9 @@ def main() -> int:
         scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
         mfma_rate = {"unit": "TFLOP/s",
                      "constant_operands": round(binding.varlen_attn_mfma_rate(False, 20000, scratch.data_ptr()), 1),
-                     "hashed_operands": round(binding.varlen_attn_mfma_rate(True, 20000, scratch.data_ptr()), 1)}
+                     "hashed_operands": round(binding.varlen_attn_mfma_rate(True, 20000, scratch.data_ptr()), 1),
+                     "lds_row_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_lds_rate(False, 20000, scratch.data_ptr()), 1),
+                     "lds_transposed_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_lds_rate(True, 20000, scratch.data_ptr()), 1)}
 
     # ---- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None

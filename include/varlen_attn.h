@@ -197,6 +197,13 @@ int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity);
 int varlen_attn_mfma_rate(int random_operands, int iterations, void* device_scratch,
                           void* hip_stream, float* tflops);
 
+/* Measurement aid: the same for the LDS reads of the attention kernels (row fragments with
+ * ds_read_b128 when transposed = 0, transposed fragments with ds_read_b64_tr_b16 when 1; 16
+ * reads in flight per wave, 8 waves per compute unit): bytes per nominal clock per compute
+ * unit, written to the HOST float.  Blocks the host. */
+int varlen_attn_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
+                         float* bytes_per_clock_per_cu);
+
 /* Static text for a status code; never NULL. */
 const char* varlen_attn_status_string(int status);
 

@@ -103,6 +103,9 @@ def lib() -> ctypes.CDLL:
         L.varlen_attn_mfma_rate.restype = ctypes.c_int
         L.varlen_attn_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
                                             ctypes.POINTER(ctypes.c_float)]
+        L.varlen_attn_lds_rate.restype = ctypes.c_int
+        L.varlen_attn_lds_rate.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
+                                           ctypes.POINTER(ctypes.c_float)]
         L.varlen_attn_profile.restype = ctypes.c_int
         L.varlen_attn_profile.argtypes = [ctypes.c_int]
         L.varlen_attn_profile_read.restype = ctypes.c_int
@@ -192,6 +195,15 @@ def varlen_attn_mfma_rate(random_operands: bool, iterations: int, device_scratch
     check(lib().varlen_attn_mfma_rate(int(bool(random_operands)), int(iterations),
                                       ctypes.c_void_p(int(device_scratch)),
                                       ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
+    return float(out.value)
+
+
+def varlen_attn_lds_rate(transposed: bool, iterations: int, device_scratch, stream=None) -> float:
+    """LDS fragment-read rate in bytes per nominal clock per CU (see the header); blocks the host."""
+    out = ctypes.c_float(0.0)
+    check(lib().varlen_attn_lds_rate(int(bool(transposed)), int(iterations),
+                                     ctypes.c_void_p(int(device_scratch)),
+                                     ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
     return float(out.value)
 
 

@@ -423,3 +423,6 @@ def test_mfma_rate_probe_runs(gpu):
         assert 50.0 < rate < 2600.0, rate
     with pytest.raises(RuntimeError):
         binding.varlen_attn_mfma_rate(False, 0, scratch.data_ptr())
+    for transposed in (False, True):
+        rate = binding.varlen_attn_lds_rate(transposed, 2000, scratch.data_ptr())
+        assert 16.0 < rate < 600.0, rate
