@@ -21,6 +21,8 @@ FLAGS = [
     # uniform-address LDS atomics from a few lanes: the optimizer's lane-by-lane reduction
     # loop costs far more than the atomic it saves
     "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
+    # the hand-placed instruction order of the inner loops is kept after register allocation
+    "-mllvm", "-enable-post-misched=0",
     "-Wno-unused-command-line-argument",
 ]
 
