@@ -113,10 +113,13 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   int mode = sorted ? 0 : 1;
 #pragma unroll 1
   for (;;) {
-    // Every (document, tile) once.  All waves walk all batches of 64 documents; tile 0 of a
-    // document is taken by one lane of the wave that owns the batch, and the further tiles of
-    // longer documents are swept by whole waves, the long documents dealt round-robin to the
-    // waves.  One call site for the per-tile code.
+    // Every (document, tile) once per direction: the lower half of the waves makes the row
+    // units, the upper half the column units.  The waves of a half walk all batches of 64
+    // documents; tile 0 of a document is taken by one lane of the wave that owns the batch,
+    // and the further tiles of longer documents are swept by whole waves, the long documents
+    // dealt round-robin to the waves of the half.  One call site for the per-tile code.
+    constexpr int kHalfWaves = kPlanThreads / 64 / 2;
+    const int d = wave / kHalfWaves, hw = wave % kHalfWaves;
     int long_rank = 0;
 #pragma unroll 1
     for (int b0 = 0; b0 < a.B; b0 += 64) {
@@ -125,7 +128,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
       const int T = (e - s + kTile - 1) / kTile;
       unsigned long long pending = __ballot(T > 1);
-      const bool own_batch = ((b0 >> 6) % (kPlanThreads / 64)) == wave;
+      const bool own_batch = ((b0 >> 6) % kHalfWaves) == hw;
       int ss = s, ee = e, i = 0, TT = own_batch ? min(T, 1) : 0;
 #pragma unroll 1
       for (;;) {
@@ -133,8 +136,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         while (__any(i < TT)) {
           if (i < TT) {
             const int row0 = ss + i * kTile;
-#pragma unroll 1
-            for (int d = 0; d < 2; ++d) {
+            {
               const int n = d == 0 ? (min(row0 + kTile, ee) - 1 - ss) / kStep + 1
                                    : (ee - row0 + kStep - 1) / kStep;
               const int nc = (n + ch[d] - 1) / ch[d], base = n / nc, rem = n % nc;
@@ -174,7 +176,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         while (pending && !found) {
           const int src = __ffsll((long long)pending) - 1;
           pending &= pending - 1;
-          if ((long_rank++ % (kPlanThreads / 64)) == wave) {
+          if ((long_rank++ % kHalfWaves) == hw) {
             ss = __shfl(s, src); ee = __shfl(e, src); TT = __shfl(T, src);
             i = 1 + lane;
             found = true;
