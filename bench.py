@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..4")
+    ap.add_argument("--seed-offset", type=int, default=0,
+                    help="added to the configuration's seed (another draw of the document lengths)")
     ap.add_argument("--buffers", type=int, default=4,
                     help="buffer sets rotated through (4 x 109 MB exceeds the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,7 +86,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    w = W.config(args.config)
+    w = W.config(args.config, seed_offset=args.seed_offset)
     vals = w.values()
     probs = [DeviceProblem(w, values=vals) for _ in range(max(1, args.buffers))]
 
@@ -110,6 +112,7 @@ def main() -> int:
     # ---- per-kernel durations: same steps again, each launch bracketed by HIP events
     kernels = {}
     roofline = None
+    split_tflops = None
     if not args.no_kernel_timing:
         binding.varlen_attn_profile(True)
         for i in range(args.steps):
@@ -118,6 +121,12 @@ def main() -> int:
         rec = binding.varlen_attn_profile_read()
         binding.varlen_attn_profile(False)
         kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in rec.items()}
+        us = lambda *names: sum(kernels[n]["avg_us"] for n in names if n in kernels)
+        pair_flops = w.head_dim * w.n_q_heads * w.pairs
+        # forward alone (with its plan) and backward alone, by the same FLOP convention
+        split_tflops = {
+            "fwd": round(4 * pair_flops / (us("plan_kernel", "fwd_kernel", "fwd_combine_kernel") * 1e-6) / 1e12, 1),
+            "bwd": round(10 * pair_flops / (us("bwd_dq_kernel", "bwd_dkv_kernel", "bwd_combine_kernel") * 1e-6) / 1e12, 1)}
         # algorithmic flops per launch: 2*d per (pair, contraction); forward S and PV;
         # dK/dV kernel S, dP, dV, dK; dQ kernel only the dQ contraction is new work
         per_pair = {"fwd_kernel": 4, "bwd_dkv_kernel": 8, "bwd_dq_kernel": 2}
@@ -206,6 +215,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in kernels.items()},
+        "fwd_bwd_tflops": split_tflops,
+        "seed": w.seed,
         "device": {"name": props.name, "cus": props.multi_processor_count},
     }
     if mfma_rate:
