@@ -71,6 +71,9 @@ extern "C" {
 /* Tuning: bits 8..15 of flags = longest chunk of a row chain, bits 16..23 = of a column chain,
  * in steps (0 = chosen by the plan from the microbatch; the plan still lengthens a value
  * whose partial results would not fit the workspace). */
+/* Tuning: bits 24..27 of flags = q heads per column unit under grouped-query attention (a
+ * divisor of Hq / Hkv; 0 = chosen by the plan: more than 1 only on large microbatches). */
+#define VARLEN_ATTN_FLAG_GROUP_HEADS(n) (((n) & 0xF) << 24)
 #define VARLEN_ATTN_FLAG_CHUNK_STEPS(row, col) ((((row) & 0xFF) << 8) | (((col) & 0xFF) << 16))
 
 typedef struct {
@@ -119,7 +122,10 @@ typedef struct {
   int32_t n_col_slots;
   int32_t sorted;          /* 1: units are in non-increasing cost order (large microbatches);
                               0: sweep order (every unit is short anyway) */
-  int32_t reserved[4];
+  int32_t col_heads_per_unit; /* grouped-query attention: q heads of one group that a column
+                                 unit sweeps one after the other (a divisor of Hq / Hkv; 1: one
+                                 unit per q head) */
+  int32_t reserved[3];
   int64_t pairs;           /* sum_b l_b (l_b + 1) / 2: (query, key) pairs inside the mask */
 } varlen_attn_plan_header;
 

@@ -26,6 +26,11 @@ FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
 
 
+def flag_group_heads(n: int) -> int:
+    """VARLEN_ATTN_FLAG_GROUP_HEADS(n): q heads per column unit under GQA (0 = plan decides)."""
+    return (int(n) & 0xF) << 24
+
+
 def flag_chunk_steps(row: int, col: int) -> int:
     """VARLEN_ATTN_FLAG_CHUNK_STEPS(row, col): longest chunk of a row / column chain (0 = plan decides)."""
     return ((int(row) & 0xFF) << 8) | ((int(col) & 0xFF) << 16)
@@ -44,7 +49,7 @@ class PlanHeader(ctypes.Structure):
                 ("n_col_combine", ctypes.c_int32), ("row_chunk_steps", ctypes.c_int32),
                 ("col_chunk_steps", ctypes.c_int32), ("n_row_slots", ctypes.c_int32),
                 ("n_col_slots", ctypes.c_int32), ("sorted", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 4),
+                ("col_heads_per_unit", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3),
                 ("pairs", ctypes.c_int64)]
 
 

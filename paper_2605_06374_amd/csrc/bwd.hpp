@@ -210,7 +210,17 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   decode_block(blockIdx.x, Hq, unit_idx, head);
   // both loads in flight together; the unit array always has max_units >= grid / Hq entries
   const int n_units = hdr->n_col_units;
-  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
+  // Grouped-query attention on large microbatches: a unit sweeps `hpu` q heads of its group
+  // one after the other (dK, dV add up in the registers).  The workgroup ids are then decoded
+  // for Hq / hpu head groups, so that the working ones still spread over all XCDs, and the
+  // unit is fetched again (one more round trip in front of a long unit).
+  const int hpu = hdr->col_heads_per_unit;
+  if (hpu > 1) {
+    decode_block(blockIdx.x, Hq / hpu, unit_idx, head);
+    head *= hpu;
+    it = units[min(unit_idx, max_units - 1)];
+  }
   if (unit_idx >= n_units) return;
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
@@ -226,6 +236,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const __bf16* dobase = d_o + (size_t)head * D;
   const float* lse_h = lse2 + (size_t)head * N;
   const float* dsum_h = dsum + (size_t)head * N;
+  int heads_left = hpu;
   const unsigned lds_q = lds_addr_of(smem), lds_do = lds_q + NS * kStageBytes;
   const unsigned lds_stat = lds_do + NS * kStageBytes + wave * kStatBytes;
   const char* stat_base = smem + 2 * NS * kStageBytes + wave * kStatBytes;
@@ -239,9 +250,6 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     dma_floats64(lse_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes, lane);
     dma_floats64(dsum_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes + 256, lane);
   };
-#pragma unroll
-  for (int st = 0; st < NS - 1; ++st) issue(st, st);
-
   bf16x8 kf[KK], vf[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
@@ -415,12 +423,19 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       stage_fast(qt, dot, stt);
     }
   };
-  for (int st = 0; st < n_steps; st += NS) {
-    body(st, std::integral_constant<int, 0>{});
-    if (st + 1 >= n_steps) break;
-    body(st + 1, std::integral_constant<int, 1>{});
+  for (;;) {
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st) issue(st, st);
+    for (int st = 0; st < n_steps; st += NS) {
+      body(st, std::integral_constant<int, 0>{});
+      if (st + 1 >= n_steps) break;
+      body(st + 1, std::integral_constant<int, 1>{});
+    }
+    wait_vm<0>();  // nothing may still be landing in LDS when the workgroup goes on or retires
+    if (--heads_left == 0) break;
+    __syncthreads();   // every wave is done with the stages before they are refilled
+    qbase += D; dobase += D; lse_h += N; dsum_h += N;
   }
-  wait_vm<0>();  // nothing may still be landing in LDS when the workgroup retires
 
   if (it.slot >= 0) {
     float* part = partials + ((size_t)it.slot * Hq + head) * 2 * frag_floats<D>();
@@ -443,7 +458,7 @@ __device__ __forceinline__ void sum_combine(int block, int n_items,
                                             const varlen_attn_combine_item* __restrict__ items,
                                             const float* __restrict__ partials,
                                             __bf16* __restrict__ out0, __bf16* __restrict__ out1,
-                                            int Hin, int G, float scale0) {
+                                            int Hin, int G, float scale0, int hpu = 1) {
   constexpr int DB = D / 32;
   constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
   const int Hout = Hin / G;
@@ -464,9 +479,11 @@ __device__ __forceinline__ void sum_combine(int block, int n_items,
   // partial number j = ch * G + gh sits (ch * Hin + gh) partial sizes after the first; four
   // loads are kept in flight, the additions stay in index order (deterministic)
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  const int n_parts = it.n_chunks * G;
+  // of the G heads of a group only every hpu-th holds a partial (its unit swept hpu heads)
+  const int Gp = G / hpu;
+  const int n_parts = it.n_chunks * Gp;
   auto part = [&](int j) {
-    return *reinterpret_cast<const f32x4*>(p0 + ((size_t)(j / G) * Hin + (j % G)) * psize);
+    return *reinterpret_cast<const f32x4*>(p0 + ((size_t)(j / Gp) * Hin + (j % Gp) * hpu) * psize);
   };
   int j = 0;
   for (; j + 4 <= n_parts; j += 4) {
@@ -491,7 +508,8 @@ bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
                    __bf16* __restrict__ dk, __bf16* __restrict__ dv, __bf16* __restrict__ dq,
                    int Hq, int Hkv, float scale, int dkv_blocks) {
   if ((int)blockIdx.x < dkv_blocks)
-    sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale);
+    sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale,
+                      hdr->col_heads_per_unit);
   else
     sum_combine<D, 1>(blockIdx.x - dkv_blocks, hdr->n_row_combine, row_items, row_partials, dq, nullptr,
                       Hq, 1, scale);

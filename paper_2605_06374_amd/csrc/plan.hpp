@@ -28,13 +28,15 @@ constexpr int kPlanBins = 1024;
 constexpr int kMinChunkSteps = 4;
 constexpr int kResidentGroups = 512;  // 256 CUs x 2 workgroups (forward, dQ)
 constexpr int kTargetUnits = 2048;
+constexpr long long kGroupSweepMinUnits = 768;  // column workgroups that must remain when units sweep several q heads
 constexpr int kNoSplitSteps = 1 << 28;
 constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: sweep order
 
 struct PlanArgs {
   const int32_t* cu;
   int B, N, Hq, g, shift, no_split;
-  int force_ch[2];  // > 0: chunk length given by the caller (tuning), per direction
+  int force_ch[2];
+  int force_hpu;    // > 0: q heads per column unit given by the caller (a divisor of g)  // > 0: chunk length given by the caller (tuning), per direction
   varlen_attn_plan_header* hdr;
   varlen_attn_unit* units[2];
   varlen_attn_combine_item* comb[2];
@@ -103,6 +105,19 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       if (a.force_ch[d] > 0) ch[d] = (int)max((long long)a.force_ch[d], sorted ? 1 : by_slots);
     }
   }
+  // Grouped-query attention: a column unit may sweep several q heads of its group (their dK,
+  // dV add up in its registers: fewer and smaller group sums afterwards) as long as enough
+  // workgroups remain.  Units of one head ~ steps / ch + tiles / 2.
+  int hpu = 1;
+  if (a.g > 1) {
+    if (a.force_hpu > 0 && a.g % a.force_hpu == 0) {
+      hpu = a.force_hpu;
+    } else {
+      const long long groups = ((long long)steps[1] / ch[1] + n_tiles / 2) * a.Hq;
+      for (int cand = 2; cand <= a.g; ++cand)
+        if (a.g % cand == 0 && groups / cand >= kGroupSweepMinUnits) hpu = cand;
+    }
+  }
   if (sorted) {
     hist[0][tid] = hist[1][tid] = 0;
     cursor[0][tid] = cursor[1][tid] = 0;
@@ -146,7 +161,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
                 if (nc > 1) atomicAdd(&split[d], nc);
               } else {
                 int slot0 = -1;
-                if (nc > 1 || (d == 1 && a.g > 1)) {
+                if (nc > 1 || (d == 1 && a.g > hpu)) {
                   slot0 = atomicAdd(&n_slots[d], nc);
                   const int ci = atomicAdd(&n_comb[d], 1);
                   if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
@@ -238,7 +253,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     hdr->n_row_slots = n_slots[0];
     hdr->n_col_slots = n_slots[1];
     hdr->sorted = sorted;
-    for (int i = 0; i < 4; ++i) hdr->reserved[i] = 0;
+    hdr->col_heads_per_unit = hpu;
+    for (int i = 0; i < 3; ++i) hdr->reserved[i] = 0;
     hdr->pairs = (int64_t)pairs;
   }
 }

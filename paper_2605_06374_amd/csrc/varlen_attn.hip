@@ -153,6 +153,7 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.no_split = (p->flags & VARLEN_ATTN_FLAG_NO_SPLIT) ? 1 : 0;
   a.force_ch[0] = (p->flags >> 8) & 0xFF;
   a.force_ch[1] = (p->flags >> 16) & 0xFF;
+  a.force_hpu = (p->flags >> 24) & 0xF;
   a.hdr = R.hdr; a.units[0] = R.row_units; a.units[1] = R.col_units;
   a.comb[0] = R.row_comb; a.comb[1] = R.col_comb;
   a.max_units = L.max_units; a.max_combine = L.max_combine;

@@ -171,11 +171,12 @@ def _check_plan(prob, w, no_split):
     cu = w.cu_seqlens
     g = w.n_q_heads // w.n_kv_heads
     assert hdr.status == 0 and hdr.pairs == oplan.pairs(cu) == w.pairs
+    assert hdr.col_heads_per_unit >= 1 and g % hdr.col_heads_per_unit == 0
     for units, comb, chains, n_slots, always_slots in (
             (plan["row_units"], plan["row_combine"], oplan.row_chain_steps(cu, 128, 64),
              hdr.n_row_slots, False),
             (plan["col_units"], plan["col_combine"], oplan.col_chain_steps(cu, 128, 64),
-             hdr.n_col_slots, g > 1)):
+             hdr.n_col_slots, g > hdr.col_heads_per_unit)):
         assert len(units) <= L.max_units and len(comb) <= L.max_combine
         by_tile = {}
         for r0, s, e, b0, b1, slot, cost, _ in units.tolist():
@@ -341,6 +342,22 @@ def test_caller_given_chunk_lengths(gpu):
     assert int(plan["row_units"][:, 6].max()) <= hdr.row_chunk_steps
     assert int(plan["col_units"][:, 6].max()) <= hdr.col_chunk_steps
     assert_close_full(prob.results(), oracle_full(w), "forced chunks")
+
+
+@pytest.mark.parametrize("heads", [1, 2, 4])
+def test_grouped_query_column_units_sweeping_heads(gpu, heads):
+    """Grouped-query dK/dV with a column unit sweeping 1, 2 or all 4 q heads of its group (forced
+    through the flag bits): plan valid, results within tolerance, with cut chains, with chains
+    kept whole, and with very short chunks."""
+    from paper_2605_06374_amd import binding
+    for lengths, hq, hkv, d, extra in (([1500, 130, 700], 4, 1, 128, 0),
+                                       ([900, 64, 1, 333], 8, 2, 64, binding.FLAG_NO_SPLIT),
+                                       ([2600], 4, 1, 128, binding.flag_chunk_steps(3, 3))):
+        w = W.custom("gqa_sweep", lengths, hq, hkv, d, seed=61 + heads)
+        prob = run_all(gpu, w, flags=binding.flag_group_heads(heads) | extra)
+        plan = _check_plan(prob, w, bool(extra & binding.FLAG_NO_SPLIT))
+        assert plan["header"].col_heads_per_unit == heads
+        assert_close_full(prob.results(), oracle_full(w), f"gqa sweep {heads} {lengths}")
 
 
 def test_bit_reproducible(gpu):
