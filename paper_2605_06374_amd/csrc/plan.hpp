@@ -27,8 +27,8 @@ constexpr int kPlanThreads = 1024;
 constexpr int kPlanBins = 1024;
 constexpr int kMinChunkSteps = 4;
 constexpr int kResidentGroups = 512;  // 256 CUs x 2 workgroups (forward, dQ)
-constexpr int kTargetUnits = 2048;
-constexpr long long kGroupSweepMinUnits = 768;  // column workgroups that must remain when units sweep several q heads
+constexpr int kTargetUnits = 512;   // (unit, head) pairs from cut chains to aim for: more cost partial-result traffic
+constexpr long long kGroupSweepMinUnits = 512;  // column workgroups that must remain when units sweep several q heads
 constexpr int kNoSplitSteps = 1 << 28;
 constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: sweep order
 
