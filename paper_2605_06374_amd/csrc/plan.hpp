@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   if (a.g > 1) {
     if (a.force_hpu > 0 && a.g % a.force_hpu == 0) {
       hpu = a.force_hpu;
-    } else {
+    } else if (!a.no_split) {   // unsplit plans must not depend on the rest of the microbatch
       const long long groups = ((long long)steps[1] / ch[1] + n_tiles / 2) * a.Hq;
       for (int cand = 2; cand <= a.g; ++cand)
         if (a.g % cand == 0 && groups / cand >= kGroupSweepMinUnits) hpu = cand;
