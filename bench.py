@@ -164,10 +164,10 @@ def main() -> int:
     if args.mfma_rate:
         scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
         mfma_rate = {"unit": "TFLOP/s",
-                     "constant_operands": round(binding.varlen_attn_mfma_rate(False, 20000, scratch.data_ptr()), 1),
-                     "hashed_operands": round(binding.varlen_attn_mfma_rate(True, 20000, scratch.data_ptr()), 1),
-                     "lds_row_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_lds_rate(False, 20000, scratch.data_ptr()), 1),
-                     "lds_transposed_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_lds_rate(True, 20000, scratch.data_ptr()), 1)}
+                     "constant_operands": round(binding.varlen_attn_bench_mfma_rate(False, 20000, scratch.data_ptr()), 1),
+                     "hashed_operands": round(binding.varlen_attn_bench_mfma_rate(True, 20000, scratch.data_ptr()), 1),
+                     "lds_row_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_bench_lds_rate(False, 20000, scratch.data_ptr()), 1),
+                     "lds_transposed_fragment_bytes_per_clk_per_cu": round(binding.varlen_attn_bench_lds_rate(True, 20000, scratch.data_ptr()), 1)}
 
     # ---- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None

@@ -58,6 +58,10 @@ extern "C" {
 #define VARLEN_ATTN_WORKSPACE_TOO_SMALL (-3)
 #define VARLEN_ATTN_LAUNCH_FAILED (-4)        /* the HIP runtime refused a launch */
 #define VARLEN_ATTN_BAD_CU_SEQLENS (-5)       /* reported by varlen_attn_check only */
+#define VARLEN_ATTN_PLAN_OVERFLOW (-6)        /* reported by varlen_attn_check only: the plan needed
+                                                 more units, reductions or partial-result slots
+                                                 than the workspace holds; no work was planned and
+                                                 no output is written */
 
 /* flags */
 #define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* bwd only: the workspace still holds the plan that a
@@ -111,7 +115,7 @@ typedef struct {
 
 /* Header at the start of the workspace, written by the plan step. */
 typedef struct {
-  int32_t status;          /* VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS */
+  int32_t status;          /* VARLEN_ATTN_OK, VARLEN_ATTN_BAD_CU_SEQLENS or VARLEN_ATTN_PLAN_OVERFLOW */
   int32_t n_row_units;     /* units of the forward / dQ direction */
   int32_t n_col_units;     /* units of the dK/dV direction */
   int32_t n_row_combine;   /* tiles whose row chain was cut */
@@ -160,12 +164,27 @@ int varlen_attn_workspace_regions(const varlen_attn_params* params,
 int varlen_attn_plan(const varlen_attn_params* params, const int32_t* cu_seqlens,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Forward: writes o and lse. */
+/* Forward (Section 5.2: the attention term of a packed micro-batch, block-diagonal mask, causal
+ * inside a document; cost proportional to sum l_i^2, Eq. 1):
+ *   S_tj = scale * q_t . k_j for cu[b] <= j <= t,  lse_t = log sum_j exp S_tj,
+ *   o_t = sum_j exp(S_tj - lse_t) v_j.
+ * q, k, v, cu_seqlens: device, read only.  o [N, Hq, d] bf16 and lse [Hq, N] fp32: device,
+ * fully overwritten.  workspace: device, at least varlen_attn_workspace_bytes(params) bytes,
+ * written (plan, partial results); it must stay untouched until a varlen_attn_bwd call with
+ * VARLEN_ATTN_FLAG_REUSE_PLAN has been enqueued, if one follows.  Returns a host-checkable status
+ * (INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, LAUNCH_FAILED) without touching the device on
+ * error; device-detected conditions are read with varlen_attn_check. */
 int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void* k,
                     const void* v, const int32_t* cu_seqlens, void* o, float* lse,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Backward: reads q, k, v, o, lse (as written by the forward) and d_o; writes dq, dk, dv.
+/* Backward of the same operation (the B chunk of the schedule DAG of Section 5.2; its cost is
+ * the quadratic term of Eq. 1 as well).  With P_tj = exp(S_tj - lse_t), D_t = sum_c dO_tc O_tc:
+ *   dV_j = sum_t P_tj dO_t,  dP_tj = dO_t . v_j,  dS_tj = P_tj (dP_tj - D_t),
+ *   dQ_t = scale * sum_j dS_tj k_j,  dK_j = scale * sum_t dS_tj q_t
+ * (dK, dV also summed over the q heads of a group).  Reads q, k, v, o, lse (as written by the
+ * forward) and d_o; dq [N, Hq, d], dk, dv [N, Hkv, d] bf16 are fully overwritten.  Workspace and
+ * status as for varlen_attn_fwd.
  * Deterministic: no atomics on floating-point data, results are bit-reproducible. */
 int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void* k,
                     const void* v, const void* o, const float* lse, const void* d_o,
@@ -173,42 +192,10 @@ int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void*
                     size_t workspace_bytes, void* hip_stream);
 
 /* Synchronises `hip_stream` and returns the status word the last plan step left in the
- * workspace (VARLEN_ATTN_OK or VARLEN_ATTN_BAD_CU_SEQLENS).  The only call that blocks. */
+ * workspace (VARLEN_ATTN_OK, VARLEN_ATTN_BAD_CU_SEQLENS or VARLEN_ATTN_PLAN_OVERFLOW), or
+ * VARLEN_ATTN_LAUNCH_FAILED when the copy fails.  `workspace` is the device pointer given to the
+ * plan / forward / backward call.  The only call that blocks. */
 int varlen_attn_check(const void* workspace, void* hip_stream);
-
-/* Optional per-kernel timing for benchmarks.  While enabled (enable != 0), every kernel
- * launch made by this library is bracketed by two HIP events recorded on the launch's own
- * stream (host-side objects; no device memory).  Calling it again, with either value,
- * drops the records collected so far.  Off by default; not thread-safe against concurrent
- * launches that should not be timed. */
-typedef struct {
-  const char* name; /* static string, e.g. "bwd_dkv_kernel" */
-  int32_t launches; /* number of launches recorded */
-  float total_ms;   /* sum of their durations */
-} varlen_attn_kernel_time;
-int varlen_attn_profile(int enable);
-
-/* Waits for the recorded events, writes one entry per kernel that was launched (at most
- * `capacity`), clears the records and returns the number of entries, or a negative status.
- * Blocks the host. */
-int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity);
-
-/* Measurement aid for benchmarks: runs, on `hip_stream`, a kernel that issues nothing but
- * bf16 MFMA 32x32x16 from registers on every SIMD (2^4 * `iterations` instructions per wave,
- * 8 waves per compute unit), twice, and writes the rate of the second run to the HOST float
- * `tflops`.  random_operands = 0: all operands 1.0; 1: hashed signs and mantissas, which is
- * what the matrix pipe sustains on real data.  `device_scratch`: any 4 writable device
- * bytes (practically never written).  Blocks the host.  Returns VARLEN_ATTN_OK,
- * VARLEN_ATTN_INVALID_ARG or VARLEN_ATTN_LAUNCH_FAILED. */
-int varlen_attn_mfma_rate(int random_operands, int iterations, void* device_scratch,
-                          void* hip_stream, float* tflops);
-
-/* Measurement aid: the same for the LDS reads of the attention kernels (row fragments with
- * ds_read_b128 when transposed = 0, transposed fragments with ds_read_b64_tr_b16 when 1; 16
- * reads in flight per wave, 8 waves per compute unit): bytes per nominal clock per compute
- * unit, written to the HOST float.  Blocks the host. */
-int varlen_attn_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
-                         float* bytes_per_clock_per_cu);
 
 /* Static text for a status code; never NULL. */
 const char* varlen_attn_status_string(int status);

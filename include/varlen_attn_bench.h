@@ -1,0 +1,59 @@
+/*
+ * varlen_attn_bench.h - benchmarking aids that are not part of the attention library's ABI.
+ *
+ * Two groups.  (1) Per-kernel timing of the attention library's own launches with HIP events:
+ * exported by libvarlen_attn.so (the launch sites live there) but declared only here, for
+ * benchmarks.  (2) Probes of what the matrix pipe and the LDS of the GPU sustain on the
+ * instruction mix of the attention kernels: exported by libvarlen_attn_bench.so, which holds
+ * nothing else.  Status codes are those of varlen_attn.h.
+ */
+#ifndef VARLEN_ATTN_BENCH_H_
+#define VARLEN_ATTN_BENCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "varlen_attn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Optional per-kernel timing for benchmarks.  While enabled (enable != 0), every kernel
+ * launch made by this library is bracketed by two HIP events recorded on the launch's own
+ * stream (host-side objects; no device memory).  Calling it again, with either value,
+ * drops the records collected so far.  Off by default; not thread-safe against concurrent
+ * launches that should not be timed. */
+typedef struct {
+  const char* name; /* static string, e.g. "bwd_dkv_kernel" */
+  int32_t launches; /* number of launches recorded */
+  float total_ms;   /* sum of their durations */
+} varlen_attn_kernel_time;
+int varlen_attn_profile(int enable);
+
+/* Waits for the recorded events, writes one entry per kernel that was launched (at most
+ * `capacity`), clears the records and returns the number of entries, or a negative status.
+ * Blocks the host. */
+int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity);
+
+/* Measurement aid for benchmarks: runs, on `hip_stream`, a kernel that issues nothing but
+ * bf16 MFMA 32x32x16 from registers on every SIMD (2^4 * `iterations` instructions per wave,
+ * 8 waves per compute unit), twice, and writes the rate of the second run to the HOST float
+ * `tflops`.  random_operands = 0: all operands 1.0; 1: hashed signs and mantissas, which is
+ * what the matrix pipe sustains on real data.  `device_scratch`: any 4 writable device
+ * bytes (practically never written).  Blocks the host.  Returns VARLEN_ATTN_OK,
+ * VARLEN_ATTN_INVALID_ARG or VARLEN_ATTN_LAUNCH_FAILED. */
+int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* device_scratch,
+                          void* hip_stream, float* tflops);
+
+/* Measurement aid: the same for the LDS reads of the attention kernels (row fragments with
+ * ds_read_b128 when transposed = 0, transposed fragments with ds_read_b64_tr_b16 when 1; 16
+ * reads in flight per wave, 8 waves per compute unit): bytes per nominal clock per compute
+ * unit, written to the HOST float.  Blocks the host. */
+int varlen_attn_bench_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
+                         float* bytes_per_clock_per_cu);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARLEN_ATTN_BENCH_H_ */

@@ -13,6 +13,7 @@ from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libvarlen_attn.so")
+BENCH_LIB_PATH = os.path.join(HERE, "libvarlen_attn_bench.so")   # measurement probes, bench.py only
 
 TILE_ROWS = 128
 STEP_ROWS = 64
@@ -22,6 +23,7 @@ UNSUPPORTED = -2
 WORKSPACE_TOO_SMALL = -3
 LAUNCH_FAILED = -4
 BAD_CU_SEQLENS = -5
+PLAN_OVERFLOW = -6
 FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
 
@@ -105,18 +107,32 @@ def lib() -> ctypes.CDLL:
         L.varlen_attn_check.argtypes = [vp, vp]
         L.varlen_attn_status_string.restype = ctypes.c_char_p
         L.varlen_attn_status_string.argtypes = [ctypes.c_int]
-        L.varlen_attn_mfma_rate.restype = ctypes.c_int
-        L.varlen_attn_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
-                                            ctypes.POINTER(ctypes.c_float)]
-        L.varlen_attn_lds_rate.restype = ctypes.c_int
-        L.varlen_attn_lds_rate.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
-                                           ctypes.POINTER(ctypes.c_float)]
         L.varlen_attn_profile.restype = ctypes.c_int
         L.varlen_attn_profile.argtypes = [ctypes.c_int]
         L.varlen_attn_profile_read.restype = ctypes.c_int
         L.varlen_attn_profile_read.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int]
         _lib = L
     return _lib
+
+
+_bench_lib = None
+
+
+def bench_lib() -> ctypes.CDLL:
+    """libvarlen_attn_bench.so (include/varlen_attn_bench.h): rate probes for benchmarks."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(BENCH_LIB_PATH):
+            raise RuntimeError(f"{BENCH_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2605_06374_amd.build`")
+        L = ctypes.CDLL(BENCH_LIB_PATH)
+        vp = ctypes.c_void_p
+        for name in ("varlen_attn_bench_mfma_rate", "varlen_attn_bench_lds_rate"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
+                                         ctypes.POINTER(ctypes.c_float)]
+        _bench_lib = L
+    return _bench_lib
 
 
 def make_params(total_tokens, num_docs, num_q_heads, num_kv_heads, head_dim, softmax_scale,
@@ -194,19 +210,19 @@ def varlen_attn_profile_read():
     return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n)}
 
 
-def varlen_attn_mfma_rate(random_operands: bool, iterations: int, device_scratch, stream=None) -> float:
+def varlen_attn_bench_mfma_rate(random_operands: bool, iterations: int, device_scratch, stream=None) -> float:
     """TFLOP/s of a pure bf16 MFMA 32x32x16 kernel (see the header); blocks the host."""
     out = ctypes.c_float(0.0)
-    check(lib().varlen_attn_mfma_rate(int(bool(random_operands)), int(iterations),
+    check(bench_lib().varlen_attn_bench_mfma_rate(int(bool(random_operands)), int(iterations),
                                       ctypes.c_void_p(int(device_scratch)),
                                       ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
     return float(out.value)
 
 
-def varlen_attn_lds_rate(transposed: bool, iterations: int, device_scratch, stream=None) -> float:
+def varlen_attn_bench_lds_rate(transposed: bool, iterations: int, device_scratch, stream=None) -> float:
     """LDS fragment-read rate in bytes per nominal clock per CU (see the header); blocks the host."""
     out = ctypes.c_float(0.0)
-    check(lib().varlen_attn_lds_rate(int(bool(transposed)), int(iterations),
+    check(bench_lib().varlen_attn_bench_lds_rate(int(bool(transposed)), int(iterations),
                                      ctypes.c_void_p(int(device_scratch)),
                                      ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
     return float(out.value)

@@ -1,4 +1,5 @@
-"""Compile csrc/varlen_attn.hip (with the .hpp files it includes) for gfx950 into libvarlen_attn.so, and the host-only
+"""Compile csrc/varlen_attn.hip (with the .hpp files it includes) for gfx950 into libvarlen_attn.so,
+csrc/varlen_attn_bench.hip (measurement probes) into libvarlen_attn_bench.so, and the host-only
 csrc/mb_time.cpp, csrc/pipeline_dag.cpp, csrc/tp_select.cpp and csrc/migration_step.cpp into
 shared libraries of the same names, next to this file."""
 from __future__ import annotations
@@ -11,6 +12,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "varlen_attn.hip")
 LIB = os.path.join(HERE, "libvarlen_attn.so")
+# measurement probes for bench.py only (matrix-pipe and LDS rates); not part of the library's ABI
+BENCH_SRC = os.path.join(HERE, "csrc", "varlen_attn_bench.hip")
+BENCH_LIB = os.path.join(HERE, "libvarlen_attn_bench.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -48,15 +52,16 @@ def build_host(verbose: bool = False) -> list:
 
 def build(verbose: bool = False) -> str:
     build_host(verbose)
-    cmd = [HIPCC] + FLAGS + ["-o", LIB, SRC]
-    if verbose:
-        print(" ".join(cmd))
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+    for lib, src in ((BENCH_LIB, BENCH_SRC), (LIB, SRC)):
+        cmd = [HIPCC] + FLAGS + ["-o", lib, src]
+        if verbose:
+            print(" ".join(cmd))
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + err)
+        if verbose and err.strip():
+            print(err)
     return LIB
 
 

@@ -239,11 +239,13 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     mode = 1;
   }
   if (tid == 0) {
-    // the capacities are worst-case bounds; an overflow cannot happen, but never trust it
+    // The capacities are worst-case bounds (tiles <= N / 128 + B; a cut chain of n > ch steps
+    // takes ceil(n / ch) <= 2 n / ch chunks, and ch was lengthened until those fit), so this
+    // cannot fail; if it ever does, it is an error of its own and nothing is planned.
     const bool ok = n_units[0] <= a.max_units && n_units[1] <= a.max_units &&
                     n_comb[0] <= a.max_combine && n_comb[1] <= a.max_combine &&
                     n_slots[0] <= a.max_slots[0] && n_slots[1] <= a.max_slots[1];
-    hdr->status = VARLEN_ATTN_OK;
+    hdr->status = ok ? VARLEN_ATTN_OK : VARLEN_ATTN_PLAN_OVERFLOW;
     hdr->n_row_units = ok ? n_units[0] : 0;
     hdr->n_col_units = ok ? n_units[1] : 0;
     hdr->n_row_combine = ok ? n_comb[0] : 0;

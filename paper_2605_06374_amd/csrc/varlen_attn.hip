@@ -9,7 +9,7 @@
 //
 // Sources: tiles.hpp (types, MFMA, LDS tile addressing and the register conventions),
 // staging.hpp (direct-to-LDS loads), plan.hpp, fragments.hpp (partial-result layout), fwd.hpp,
-// bwd.hpp, mfma_rate.hpp; this file holds the profiler, the host side and the C ABI.
+// bwd.hpp; this file holds the profiler, the host side and the C ABI.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "varlen_attn.h"
+#include "varlen_attn_bench.h"   // declares the event profiler exported from here
 
 #include "tiles.hpp"
 #include "staging.hpp"
@@ -27,7 +28,6 @@
 #include "fragments.hpp"
 #include "fwd.hpp"
 #include "bwd.hpp"
-#include "mfma_rate.hpp"
 
 namespace {
 
@@ -87,6 +87,8 @@ bool layout_of(const varlen_attn_params* p, varlen_attn_workspace_layout* L, int
   const long long tiles = (long long)p->total_tokens / kTile + p->num_docs;
   if (tiles > (1 << 24)) return false;
   const int Hq = p->num_q_heads, g = Hq / p->num_kv_heads;
+  // every grid (units x heads, reduction blocks: tiles x heads x 2 tensors x 16) stays below 2^31
+  if (tiles * Hq * 48 >= (1ll << 31)) return false;
   const long long cap = std::min<long long>((kTargetUnits + Hq - 1) / Hq, 8 * tiles);
   *slots_cap = (int)cap;
   L->max_units = (int)(tiles + cap);
@@ -205,7 +207,7 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
   if (split || Hq != Hkv) {
     constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
-    const int dkv_blocks = L.max_combine * Hkv * 2 * kBlocksPerItem;
+    const int dkv_blocks = L.max_combine * Hkv * 2 * kBlocksPerItem;   // bounded by layout_of
     const int dq_blocks = split ? L.max_combine * Hq * kBlocksPerItem : 0;
     ScopedKernelTimer timer(kBwdCombine, stream);
     bwd_combine_kernel<D><<<dim3((unsigned)(dkv_blocks + dq_blocks)), kThreads, 0, stream>>>(
@@ -327,68 +329,6 @@ int varlen_attn_profile_read(varlen_attn_kernel_time* out, int capacity) {
   return n;
 }
 
-int varlen_attn_mfma_rate(int random_operands, int iterations, void* device_scratch,
-                          void* hip_stream, float* tflops) {
-  if (!device_scratch || !tflops || iterations < 1 || iterations > (1 << 24))
-    return VARLEN_ATTN_INVALID_ARG;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-    return VARLEN_ATTN_LAUNCH_FAILED;
-  hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
-  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
-  const unsigned grid = 2u * (unsigned)cus;
-  float ms = 0.f;
-  bool ok = true;
-  for (int pass = 0; pass < 2 && ok; ++pass) {   // the first pass warms the clocks up
-    ok = hipEventRecord(e0, stream) == hipSuccess;
-    mfma_rate_kernel<<<dim3(grid), kThreads, 0, stream>>>(static_cast<float*>(device_scratch),
-                                                          iterations, random_operands);
-    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
-         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-  }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
-  const double flops = (double)grid * (kThreads / 64) * (double)iterations * 16.0 * 32768.0;
-  *tflops = (float)(flops / (ms * 1e-3) / 1e12);
-  return VARLEN_ATTN_OK;
-}
-
-int varlen_attn_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
-                         float* bytes_per_clock_per_cu) {
-  if (!device_scratch || !bytes_per_clock_per_cu || iterations < 1 || iterations > (1 << 24))
-    return VARLEN_ATTN_INVALID_ARG;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  int dev = 0, cus = 0, khz = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess || khz <= 0)
-    return VARLEN_ATTN_LAUNCH_FAILED;
-  hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
-  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
-  const unsigned grid = 2u * (unsigned)cus;
-  float ms = 0.f;
-  bool ok = true;
-  for (int pass = 0; pass < 2 && ok; ++pass) {
-    ok = hipEventRecord(e0, stream) == hipSuccess;
-    lds_rate_kernel<<<dim3(grid), kThreads, 0, stream>>>(static_cast<float*>(device_scratch),
-                                                         iterations, transposed);
-    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
-         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-  }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
-  // 16 fragments of 1 KiB per wave and iteration, 8 waves per CU; clocks at the nominal rate
-  const double bytes_per_cu = 8.0 * (double)iterations * 16.0 * 1024.0;
-  *bytes_per_clock_per_cu = (float)(bytes_per_cu / (ms * 1e-3 * khz * 1e3));
-  return VARLEN_ATTN_OK;
-}
-
 const char* varlen_attn_status_string(int status) {
   switch (status) {
     case VARLEN_ATTN_OK: return "ok";
@@ -397,6 +337,7 @@ const char* varlen_attn_status_string(int status) {
     case VARLEN_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small";
     case VARLEN_ATTN_LAUNCH_FAILED: return "kernel launch failed";
     case VARLEN_ATTN_BAD_CU_SEQLENS: return "malformed cu_seqlens";
+    case VARLEN_ATTN_PLAN_OVERFLOW: return "plan does not fit the workspace";
     default: return "unknown status";
   }
 }

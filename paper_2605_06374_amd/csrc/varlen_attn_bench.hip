@@ -1,0 +1,77 @@
+// Measurement probes for benchmarks (not part of the attention library): what the matrix pipe
+// and the LDS of this GPU sustain on the instruction mix of the attention kernels.  Built into
+// libvarlen_attn_bench.so; declared in include/varlen_attn_bench.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "varlen_attn_bench.h"
+
+#include "tiles.hpp"
+#include "staging.hpp"
+#include "mfma_rate.hpp"
+
+extern "C" {
+
+int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* device_scratch,
+                          void* hip_stream, float* tflops) {
+  if (!device_scratch || !tflops || iterations < 1 || iterations > (1 << 24))
+    return VARLEN_ATTN_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return VARLEN_ATTN_LAUNCH_FAILED;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
+  const unsigned grid = 2u * (unsigned)cus;
+  float ms = 0.f;
+  bool ok = true;
+  for (int pass = 0; pass < 2 && ok; ++pass) {   // the first pass warms the clocks up
+    ok = hipEventRecord(e0, stream) == hipSuccess;
+    mfma_rate_kernel<<<dim3(grid), kThreads, 0, stream>>>(static_cast<float*>(device_scratch),
+                                                          iterations, random_operands);
+    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
+         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
+  const double flops = (double)grid * (kThreads / 64) * (double)iterations * 16.0 * 32768.0;
+  *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+  return VARLEN_ATTN_OK;
+}
+
+int varlen_attn_bench_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
+                         float* bytes_per_clock_per_cu) {
+  if (!device_scratch || !bytes_per_clock_per_cu || iterations < 1 || iterations > (1 << 24))
+    return VARLEN_ATTN_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess || khz <= 0)
+    return VARLEN_ATTN_LAUNCH_FAILED;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
+  const unsigned grid = 2u * (unsigned)cus;
+  float ms = 0.f;
+  bool ok = true;
+  for (int pass = 0; pass < 2 && ok; ++pass) {
+    ok = hipEventRecord(e0, stream) == hipSuccess;
+    lds_rate_kernel<<<dim3(grid), kThreads, 0, stream>>>(static_cast<float*>(device_scratch),
+                                                         iterations, transposed);
+    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
+         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
+  // 16 fragments of 1 KiB per wave and iteration, 8 waves per CU; clocks at the nominal rate
+  const double bytes_per_cu = 8.0 * (double)iterations * 16.0 * 1024.0;
+  *bytes_per_clock_per_cu = (float)(bytes_per_cu / (ms * 1e-3 * khz * 1e3));
+  return VARLEN_ATTN_OK;
+}
+
+}  // extern "C"

@@ -11,6 +11,12 @@ from paper_2605_06374_amd import workloads as W
 TOL_O = 1e-2      # max |x - y| / max |y|, forward output
 TOL_GRAD = 2e-2   # same, dQ / dK / dV
 TOL_LSE = 1e-3    # |x - y| <= TOL_LSE * max(1, |y|)
+# Element-wise gate: |x_i - y_i| <= TOL_E2 * max(|y_i|, rms of the element's d-vector).  One
+# bf16 rounding of the output is 2^-9 = 2e-3 of |y_i|; the rounded P / dS operands add errors
+# of the size of the vector's rms, a few 1e-3 each; the worst element of millions is bounded here
+# by 2.5 times the tensor-scale tolerance.
+TOL_E2_O = 2.5e-2
+TOL_E2_GRAD = 5e-2
 
 
 def f64_values(w, values=None):
@@ -46,6 +52,8 @@ def assert_close_full(got, ref, label=""):
         assert np.isfinite(got[name]).all(), f"{label} {name}: non-finite output"
         errs[name] = (e1(got[name], ref[name]), e2(got[name], ref[name]))
         assert errs[name][0] <= tol, f"{label} {name}: E1 {errs[name][0]:.3e} > {tol}"
+        tol2 = TOL_E2_O if name == "o" else TOL_E2_GRAD
+        assert errs[name][1] <= tol2, f"{label} {name}: E2 {errs[name][1]:.3e} > {tol2}"
     dl = np.abs(got["lse"] - ref["lse"]) / np.maximum(1.0, np.abs(ref["lse"]))
     assert dl.max() <= TOL_LSE, f"{label} lse: {dl.max():.3e}"
     errs["lse"] = (float(dl.max()), float(dl.max()))

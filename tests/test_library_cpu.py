@@ -11,8 +11,8 @@ from paper_2605_06374_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "varlen_attn.h")).read()
+def declared_functions(header="varlen_attn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(varlen_attn_[a-z_]+)\s*\(", text)))
 
@@ -24,6 +24,31 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    # the product header declares no measurement aid
+    assert not [n for n in names if "rate" in n or "profile" in n or "bench" in n]
+
+
+def test_bench_header_symbols_are_exported_by_the_two_libraries():
+    """include/varlen_attn_bench.h: the event profiler lives in the attention library (its
+    launch sites are there), the rate probes in a library of their own."""
+    names = declared_functions("varlen_attn_bench.h")
+    assert {"varlen_attn_profile", "varlen_attn_profile_read", "varlen_attn_bench_mfma_rate",
+            "varlen_attn_bench_lds_rate"} <= set(names)
+    lib, bench = ctypes.CDLL(B.LIB_PATH), ctypes.CDLL(B.BENCH_LIB_PATH)
+    for n in names:
+        owner = bench if n.startswith("varlen_attn_bench_") else lib
+        assert hasattr(owner, n), n
+    assert not hasattr(lib, "varlen_attn_bench_mfma_rate")
+
+
+def test_status_strings():
+    seen = set()
+    for code in (B.OK, B.INVALID_ARG, B.UNSUPPORTED, B.WORKSPACE_TOO_SMALL, B.LAUNCH_FAILED,
+                 B.BAD_CU_SEQLENS, B.PLAN_OVERFLOW):
+        text = B.varlen_attn_status_string(code)
+        assert text and text != "unknown status" and text not in seen
+        seen.add(text)
+    assert B.varlen_attn_status_string(-99) == "unknown status"
 
 
 def test_struct_sizes_match_header():
@@ -98,3 +123,52 @@ def test_status_strings():
         seen.add(s)
     assert len(seen) == 6
     assert B.varlen_attn_status_string(-99) == "unknown status"
+
+
+# ------------------------------------------------------------------ capacities of the workspace
+def _adversarial_cu_lists():
+    import numpy as np
+    rng = np.random.default_rng(7)
+    yield [1] * 5000                                   # many one-token documents
+    yield [129] * 200                                  # every document spills one row into a second tile
+    yield [100000]                                     # one huge document
+    yield [0, 0, 40000, 0, 1, 127, 128, 129, 0]        # empties next to a long one
+    yield [65] * 300 + [9000]
+    for _ in range(6):
+        yield [int(x) for x in rng.integers(0, 700, size=int(rng.integers(1, 400)))] + [1]
+
+
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (4, 4), (8, 1), (32, 8)])
+def test_workspace_capacities_bound_every_plan(hq, hkv):
+    """The capacities depend on (N, B, Hq, Hkv, d) only.  Against the oracle's tile set and
+    chain lengths: every tile fits the reduction list; for every chunk length whose cut chains
+    fit the slot budget, the units fit the unit arrays (uncut tiles + slots); the chunk length
+    the plan starts from (2 * steps / ch <= budget) always fits; and some chunk length fits."""
+    from itertools import accumulate
+    from oracle import plan as oplan
+    for lengths in _adversarial_cu_lists():
+        cu = [0] + list(accumulate(lengths))
+        n = cu[-1]
+        p = B.make_params(n, len(lengths), hq, hkv, 128, 0.1)
+        L = B.varlen_attn_workspace_regions(p)
+        cap = L.max_row_slots
+        tiles = oplan.row_tiles(cu, B.TILE_ROWS)
+        assert len(tiles) <= L.max_combine <= n // B.TILE_ROWS + len(lengths)
+        for chains in (oplan.row_chain_steps(cu, B.TILE_ROWS, B.STEP_ROWS),
+                       oplan.col_chain_steps(cu, B.TILE_ROWS, B.STEP_ROWS)):
+            lens = list(chains.values())
+            steps = sum(lens)
+            assert len(lens) == len(tiles)
+            fitting = 0
+            for ch in sorted(set([1, 2, 3, 4, 5, 8, 13, 64, 1000] + lens)):
+                slots = sum(-(-x // ch) for x in lens if x > ch)
+                units = sum(-(-x // ch) for x in lens)
+                assert slots <= 2 * steps // ch + 1          # what the plan's first guess relies on
+                if slots <= cap:
+                    fitting += 1
+                    assert units <= L.max_units
+                    if hq > hkv:                            # grouped: every tile takes slots
+                        assert units <= L.max_col_slots
+                if 2 * steps <= ch * cap:
+                    assert slots <= cap
+            assert fitting >= 1 and sum(-(-x // max(lens)) for x in lens if x > max(lens)) == 0

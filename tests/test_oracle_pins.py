@@ -371,3 +371,39 @@ def test_bf16_rounding_helpers():
     ref = torch.tensor(x).to(torch.bfloat16)
     assert np.array_equal(bits.view(np.int16), ref.view(torch.int16).numpy())
     assert np.array_equal(W.bf16_bits_to_f32(bits), ref.float().numpy())
+
+
+# ------------------------------------------------------------------ chains of the plan
+@pytest.mark.parametrize("tile,step", [(128, 64), (8, 4), (6, 3), (4, 4)])
+def test_chain_steps_against_brute_force_over_the_mask(tile, step):
+    """row_chain_steps / col_chain_steps against a count over the explicit mask: for every
+    tile, the steps (of `step` keys counted from the document start, resp. `step` queries
+    counted from the tile's first row) that hold at least one allowed (t, j)."""
+    from oracle import plan as oplan
+    rng = np.random.default_rng(tile * 100 + step)
+    cases = [[0], [1], [0, 0, 1, 0], [step, step + 1, tile, tile + 1, tile - 1, 1, 0, 2 * tile + 1],
+             [3 * tile + step + 1]]
+    for _ in range(12):
+        cases.append([int(x) for x in rng.integers(0, 3 * tile + 2, size=int(rng.integers(1, 7)))])
+    for lengths in cases:
+        cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+        n = int(cu[-1])
+        doc = np.array(oplan.doc_of_token(cu), dtype=np.int64)
+        t_idx, j_idx = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+        allowed = (doc[t_idx] == doc[j_idx]) & (j_idx <= t_idx) if n else np.zeros((0, 0), bool)
+        want_row, want_col = {}, {}
+        for b in range(len(lengths)):
+            s, e = int(cu[b]), int(cu[b + 1])
+            for r0 in range(s, e, tile):
+                r1 = min(r0 + tile, e)
+                # keys seen by some query of the tile, in steps from the document start
+                keys = np.nonzero(allowed[r0:r1].any(axis=0))[0]
+                want_row[(r0, s, e)] = len(set(int((j - s) // step) for j in keys))
+                # queries that see some key of the tile, in steps from the tile's first row
+                queries = np.nonzero(allowed[:, r0:r1].any(axis=1))[0]
+                want_col[(r0, s, e)] = len(set(int((t - r0) // step) for t in queries))
+                # both sets are gap-free ranges starting at step 0
+                assert set(int((j - s) // step) for j in keys) == set(range(want_row[(r0, s, e)]))
+                assert set(int((t - r0) // step) for t in queries) == set(range(want_col[(r0, s, e)]))
+        assert oplan.row_chain_steps(cu, tile, step) == want_row, lengths
+        assert oplan.col_chain_steps(cu, tile, step) == want_col, lengths
