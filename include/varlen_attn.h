@@ -91,8 +91,8 @@ typedef struct {
 } varlen_attn_params;
 
 /* Work unit of the plan: a chunk [step_begin, step_end) of the chain of one tile.  Units are
- * ordered by non-increasing cost (longest job first); the order among equal costs is not
- * defined. */
+ * ordered by non-increasing cost class (cost - 1) >> class_shift of their direction (longest
+ * jobs first; 32 classes at most); the order inside a class is not defined. */
 typedef struct {
   int32_t row0;       /* first token of the tile */
   int32_t doc_start;  /* cu[b]   */
@@ -124,12 +124,12 @@ typedef struct {
   int32_t col_chunk_steps; /* longest chunk allowed in a column chain */
   int32_t n_row_slots;
   int32_t n_col_slots;
-  int32_t sorted;          /* 1: units are in non-increasing cost order (large microbatches);
-                              0: sweep order (every unit is short anyway) */
+  int32_t row_class_shift; /* row units are in non-increasing order of (cost - 1) >> row_class_shift */
   int32_t col_heads_per_unit; /* grouped-query attention: q heads of one group that a column
                                  unit sweeps one after the other (a divisor of Hq / Hkv; 1: one
                                  unit per q head) */
-  int32_t reserved[3];
+  int32_t col_class_shift; /* the same for the column units */
+  int32_t reserved[2];
   int64_t pairs;           /* sum_b l_b (l_b + 1) / 2: (query, key) pairs inside the mask */
 } varlen_attn_plan_header;
 

@@ -50,8 +50,9 @@ class PlanHeader(ctypes.Structure):
                 ("n_col_units", ctypes.c_int32), ("n_row_combine", ctypes.c_int32),
                 ("n_col_combine", ctypes.c_int32), ("row_chunk_steps", ctypes.c_int32),
                 ("col_chunk_steps", ctypes.c_int32), ("n_row_slots", ctypes.c_int32),
-                ("n_col_slots", ctypes.c_int32), ("sorted", ctypes.c_int32),
-                ("col_heads_per_unit", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3),
+                ("n_col_slots", ctypes.c_int32), ("row_class_shift", ctypes.c_int32),
+                ("col_heads_per_unit", ctypes.c_int32), ("col_class_shift", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2),
                 ("pairs", ctypes.c_int64)]
 
 

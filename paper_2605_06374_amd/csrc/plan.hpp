@@ -16,40 +16,56 @@ namespace {
 // once (kResidentGroups workgroups: one round, no second wave of stragglers); otherwise long
 // enough that about kTargetUnits pairs exist; and always such that the partial-result slots
 // fit the workspace.
-// Small microbatches (every unit is short anyway) are written in sweep order; large ones are
-// placed by a counting sort on cost, descending (longest job first).
 //
-// The kernel runs once per microbatch on a single compute unit with a cold instruction
-// cache, so its latency follows the amount of code it executes: the two directions and the
-// two passes share one copy of the per-tile code (loops deliberately not unrolled).
+// Units are placed longest first by cost class (kPlanClasses classes of equal width over the
+// chunk lengths that occur): the hardware hands workgroups out in index order, so this is
+// longest-job-first list scheduling.  The order inside a class is not defined.
+//
+// The kernel runs once per microbatch on a single compute unit, in front of everything else,
+// so its latency is what counts: one thread per document, then one thread per tile (found by
+// bisection in the running tile count of the documents), class counters per wave in LDS so that
+// the same-address atomics of a wave stay inside the wave, and two sweeps over the tiles
+// (count, then place) that run the same code.
 // ----------------------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
-constexpr int kPlanBins = 1024;
+constexpr int kPlanWaves = kPlanThreads / 64;
+constexpr int kPlanClasses = 32;
 constexpr int kMinChunkSteps = 4;
 constexpr int kResidentGroups = 512;  // 256 CUs x 2 workgroups (forward, dQ)
 constexpr int kTargetUnits = 512;   // (unit, head) pairs from cut chains to aim for: more cost partial-result traffic
 constexpr long long kGroupSweepMinUnits = 512;  // column workgroups that must remain when units sweep several q heads
 constexpr int kNoSplitSteps = 1 << 28;
-constexpr long long kSortAboveSteps = 1024;  // (tile step, head) pairs; below: sweep order
 
 struct PlanArgs {
   const int32_t* cu;
-  int B, N, Hq, g, shift, no_split;
-  int force_ch[2];
-  int force_hpu;    // > 0: q heads per column unit given by the caller (a divisor of g)  // > 0: chunk length given by the caller (tuning), per direction
+  int B, N, Hq, g, no_split;
+  int force_ch[2];  // > 0: chunk length given by the caller (tuning), per direction
+  int force_hpu;    // > 0: q heads per column unit given by the caller (a divisor of g)
   varlen_attn_plan_header* hdr;
   varlen_attn_unit* units[2];
   varlen_attn_combine_item* comb[2];
   int max_units, max_combine, max_slots[2], slots_cap;
+  int32_t* status_copy;   // optional second place for the status word (device), or null
 };
 
+// inclusive sum over the lanes of a wave
+__device__ __forceinline__ int wave_inclusive_sum(int v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(v, off);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
 __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
-  __shared__ int bad;
-  __shared__ int hist[2][kPlanBins];    // units per cost bucket, then start offsets
-  __shared__ int cursor[2][kPlanBins];
-  __shared__ int wsum[kPlanThreads / 64];
+  __shared__ int doc_first_tile[kPlanThreads + 1];  // running tile count of the batch's documents
+  __shared__ int doc_s[kPlanThreads], doc_e[kPlanThreads];
+  __shared__ int hist[2][kPlanClasses][kPlanWaves];    // units per (direction, class, wave), then cursors
+  __shared__ int class_total[2][kPlanClasses];
+  __shared__ int wave_sum[kPlanWaves];
   __shared__ unsigned long long pairs, steps[2];
-  __shared__ int n_tiles;
+  __shared__ int n_tiles, bad, max_chain[2];
   __shared__ int split[2], n_units[2], n_slots[2], n_comb[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* cu = a.cu;
@@ -58,11 +74,12 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     pairs = steps[0] = steps[1] = 0;
     n_tiles = 0;
   }
-  if (tid < 2) split[tid] = n_units[tid] = n_slots[tid] = n_comb[tid] = 0;
+  if (tid < 2) split[tid] = n_units[tid] = n_slots[tid] = n_comb[tid] = max_chain[tid] = 0;
   __syncthreads();
+  // ---- totals over the documents: pairs, steps of both directions, tiles, longest chains
   {
     unsigned long long my_pairs = 0, my_r = 0, my_c = 0;
-    int my_bad = 0, my_tiles = 0;
+    int my_bad = 0, my_tiles = 0, my_max = 0;
 #pragma unroll 1
     for (int b = tid; b < a.B; b += kPlanThreads) {
       const long long l = (long long)cu[b + 1] - cu[b];
@@ -72,27 +89,32 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       my_r += (unsigned long long)(T * (T - 1) + S);
       my_c += (unsigned long long)(T * S - T * (T - 1));
       my_tiles += (int)T;
+      my_max = max(my_max, (int)S);
     }
     if (my_bad) bad = 1;
-    if (my_pairs) { atomicAdd(&pairs, my_pairs); atomicAdd(&steps[0], my_r); atomicAdd(&steps[1], my_c); atomicAdd(&n_tiles, my_tiles); }
+    if (my_pairs) {
+      atomicAdd(&pairs, my_pairs); atomicAdd(&steps[0], my_r); atomicAdd(&steps[1], my_c);
+      atomicAdd(&n_tiles, my_tiles);
+      atomicMax(&max_chain[0], my_max);   // the longest row and column chains are both ceil(l / 64)
+    }
   }
   __syncthreads();
   varlen_attn_plan_header* hdr = a.hdr;
   if (bad) {
     if (tid < (int)(sizeof(varlen_attn_plan_header) / 4)) reinterpret_cast<int32_t*>(hdr)[tid] = 0;
     __syncthreads();
-    if (tid == 0) hdr->status = VARLEN_ATTN_BAD_CU_SEQLENS;
+    if (tid == 0) {
+      hdr->status = VARLEN_ATTN_BAD_CU_SEQLENS;
+      if (a.status_copy) *a.status_copy = VARLEN_ATTN_BAD_CU_SEQLENS;
+    }
     return;
   }
-  const bool sorted = (long long)steps[0] * a.Hq > kSortAboveSteps;
   int ch[2];
 #pragma unroll
   for (int d = 0; d < 2; ++d) {
     ch[d] = kNoSplitSteps;
     if (!a.no_split) {
-      // 2 * steps / ch bounds the slots of the chains that get cut (each has > ch steps)
       const long long by_units = (long long)((steps[d] * a.Hq + kTargetUnits - 1) / kTargetUnits);
-      const long long by_slots = (long long)((2 * steps[d] + a.slots_cap - 1) / a.slots_cap);
       // Units of one head ~ steps / ch + tiles / 2 (a cut chain rarely divides evenly).  If
       // the tiles leave room, take the shortest chunks that keep every unit resident at once;
       // dK/dV partials are twice as large and its kernel is insensitive here: twice as long.
@@ -100,9 +122,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       long long by_fill = 0;
       if (room >= kResidentGroups / a.Hq / 4 && room > 0)
         by_fill = (d + 1) * (((long long)steps[d] + room - 1) / room);
-      const long long floor_ch = max((long long)kMinChunkSteps, by_fill);
-      ch[d] = (int)max(floor_ch, sorted ? by_units : max(by_units, by_slots));
-      if (a.force_ch[d] > 0) ch[d] = (int)max((long long)a.force_ch[d], sorted ? 1 : by_slots);
+      ch[d] = (int)max(max((long long)kMinChunkSteps, by_fill), by_units);
+      if (a.force_ch[d] > 0) ch[d] = a.force_ch[d];
     }
   }
   // Grouped-query attention: a column unit may sweep several q heads of its group (their dK,
@@ -118,122 +139,116 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         if (a.g % cand == 0 && groups / cand >= kGroupSweepMinUnits) hpu = cand;
     }
   }
-  if (sorted) {
-    hist[0][tid] = hist[1][tid] = 0;
-    cursor[0][tid] = cursor[1][tid] = 0;
-  }
-  __syncthreads();
+  const int longest = max_chain[0];
 
-  // mode 0: count unit costs (sorted plans only); mode 1: write units.
-  int mode = sorted ? 0 : 1;
+  // mode 0: count the units of every cost class (and the chunks of cut chains); mode 1: place.
+  int mode = 0, shift[2] = {0, 0};
 #pragma unroll 1
   for (;;) {
-    // Every (document, tile) once per direction: the lower half of the waves makes the row
-    // units, the upper half the column units.  The waves of a half walk all batches of 64
-    // documents; tile 0 of a document is taken by one lane of the wave that owns the batch,
-    // and the further tiles of longer documents are swept by whole waves, the long documents
-    // dealt round-robin to the waves of the half.  One call site for the per-tile code.
-    constexpr int kHalfWaves = kPlanThreads / 64 / 2;
-    const int d = wave / kHalfWaves, hw = wave % kHalfWaves;
-    int long_rank = 0;
-#pragma unroll 1
-    for (int b0 = 0; b0 < a.B; b0 += 64) {
-      const int b = b0 + lane;
-      int s = 0, e = 0;
-      if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
-      const int T = (e - s + kTile - 1) / kTile;
-      unsigned long long pending = __ballot(T > 1);
-      const bool own_batch = ((b0 >> 6) % kHalfWaves) == hw;
-      int ss = s, ee = e, i = 0, TT = own_batch ? min(T, 1) : 0;
-#pragma unroll 1
-      for (;;) {
-#pragma unroll 1
-        while (__any(i < TT)) {
-          if (i < TT) {
-            const int row0 = ss + i * kTile;
-            {
-              const int n = d == 0 ? (min(row0 + kTile, ee) - 1 - ss) / kStep + 1
-                                   : (ee - row0 + kStep - 1) / kStep;
-              const int nc = (n + ch[d] - 1) / ch[d], base = n / nc, rem = n % nc;
-              if (mode == 0) {
-                atomicAdd(&hist[d][(base - 1) >> a.shift], nc - rem);
-                if (rem) atomicAdd(&hist[d][base >> a.shift], rem);
-                if (nc > 1) atomicAdd(&split[d], nc);
-              } else {
-                int slot0 = -1;
-                if (nc > 1 || (d == 1 && a.g > hpu)) {
-                  slot0 = atomicAdd(&n_slots[d], nc);
-                  const int ci = atomicAdd(&n_comb[d], 1);
-                  if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
-                    a.comb[d][ci] = varlen_attn_combine_item{row0, ee, slot0, nc};
-                }
-                int pos0 = sorted ? 0 : atomicAdd(&n_units[d], nc);
-#pragma unroll 1
-                for (int c = 0; c < nc; ++c) {
-                  const int b_ = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
-                  int pos = pos0 + c;
-                  if (sorted) {
-                    const int k = (len - 1) >> a.shift;
-                    pos = hist[d][k] + atomicAdd(&cursor[d][k], 1);
-                  }
-                  if (pos < a.max_units)
-                    a.units[d][pos] = varlen_attn_unit{row0, ss, ee, b_, b_ + len,
-                                                       slot0 < 0 ? -1 : slot0 + c, len, 0};
-                }
-              }
-            }
-          }
-          i += 64;
-        }
-        // next long document dealt to this wave
-        bool found = false;
-#pragma unroll 1
-        while (pending && !found) {
-          const int src = __ffsll((long long)pending) - 1;
-          pending &= pending - 1;
-          if ((long_rank++ % kHalfWaves) == hw) {
-            ss = __shfl(s, src); ee = __shfl(e, src); TT = __shfl(T, src);
-            i = 1 + lane;
-            found = true;
-          }
-        }
-        if (!found) break;
+    if (mode == 0) {
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        shift[d] = 0;
+        while ((min(ch[d], longest) - 1) >> shift[d] >= kPlanClasses) ++shift[d];
       }
-    }
-    __syncthreads();
-    if (mode == 1) break;
-    // sorted plans: lengthen the chunks until the cut chains fit, then turn the histograms
-    // into start offsets (exclusive suffix sums: longest first)
-    const bool fit0 = split[0] <= a.slots_cap, fit1 = split[1] <= a.slots_cap;
-    __syncthreads();
-    if (!(fit0 && fit1)) {
-      if (!fit0) ch[0] *= 2;
-      if (!fit1) ch[1] *= 2;
-      hist[0][tid] = hist[1][tid] = 0;
+      reinterpret_cast<int*>(hist)[tid] = 0;   // 2 x 32 x 16 = 1024 counters
       if (tid < 2) split[tid] = 0;
       __syncthreads();
-      continue;
     }
 #pragma unroll 1
-    for (int d = 0; d < 2; ++d) {
-      const int own = hist[d][tid];
-      int v = own;
+    for (int b0 = 0; b0 < a.B; b0 += kPlanThreads) {
+      // ---- this batch's documents: running tile count (exclusive) by a workgroup-wide scan
+      {
+        const int b = b0 + tid;
+        int s = 0, e = 0;
+        if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
+        const int T = (e - s + kTile - 1) / kTile;
+        const int incl = wave_inclusive_sum(T, lane);
+        if (lane == 63) wave_sum[wave] = incl;
+        doc_s[tid] = s; doc_e[tid] = e;
+        __syncthreads();
+        int before = 0;
 #pragma unroll 1
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_down(v, off);
-        if (lane + off < 64) v += o;
+        for (int w = 0; w < wave; ++w) before += wave_sum[w];
+        doc_first_tile[tid + 1] = before + incl;
+        if (tid == 0) doc_first_tile[0] = 0;
+        __syncthreads();
       }
-      if (lane == 0) wsum[wave] = v;
+      const int batch_tiles = doc_first_tile[kPlanThreads];
+#pragma unroll 1
+      for (int t = tid; t < batch_tiles; t += kPlanThreads) {
+        // document of tile t: the last one whose first tile is <= t (documents without tiles
+        // repeat the value of their successor and are skipped by taking the last)
+        int lo = 0, hi = kPlanThreads;   // doc_first_tile[lo] <= t < doc_first_tile[hi]
+#pragma unroll 1
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (doc_first_tile[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int ss = doc_s[lo], ee = doc_e[lo];
+        const int row0 = ss + (t - doc_first_tile[lo]) * kTile;
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+          const int n = d == 0 ? (min(row0 + kTile, ee) - 1 - ss) / kStep + 1
+                               : (ee - row0 + kStep - 1) / kStep;
+          const int nc = (n + ch[d] - 1) / ch[d], base = n / nc, rem = n % nc;
+          // nc - rem chunks of `base` steps, rem chunks of base + 1 (those come first in the chain)
+          int* h_lo = &hist[d][(base - 1) >> shift[d]][wave];
+          int* h_hi = &hist[d][base >> shift[d]][wave];
+          if (mode == 0) {
+            atomicAdd(h_lo, nc - rem);
+            if (rem) atomicAdd(h_hi, rem);
+            if (nc > 1) atomicAdd(&split[d], nc);
+          } else {
+            int slot0 = -1;
+            if (nc > 1 || (d == 1 && a.g > hpu)) {
+              slot0 = atomicAdd(&n_slots[d], nc);
+              const int ci = atomicAdd(&n_comb[d], 1);
+              if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
+                a.comb[d][ci] = varlen_attn_combine_item{row0, ee, slot0, nc};
+            }
+            int pos_lo = atomicAdd(h_lo, nc - rem);
+            int pos_hi = rem ? atomicAdd(h_hi, rem) : 0;
+#pragma unroll 1
+            for (int c = 0; c < nc; ++c) {
+              const int first = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
+              const int pos = c < rem ? pos_hi++ : pos_lo++;
+              if (pos < a.max_units)
+                a.units[d][pos] = varlen_attn_unit{row0, ss, ee, first, first + len,
+                                                   slot0 < 0 ? -1 : slot0 + c, len, 0};
+            }
+          }
+        }
+      }
+      __syncthreads();   // the batch arrays are rewritten by the next batch
+    }
+    if (mode == 1) break;
+    // lengthen the chunks until the cut chains fit their slots
+    const bool fit0 = split[0] <= a.slots_cap, fit1 = split[1] <= a.slots_cap;
+    if (!(fit0 && fit1)) {
       __syncthreads();
-      int above = 0, total = 0;
-#pragma unroll 1
-      for (int w = 0; w < kPlanThreads / 64; ++w) {
-        const int x = wsum[w];
-        total += x;
-        if (w > wave) above += x;
+      if (!fit0) ch[0] *= 2;
+      if (!fit1) ch[1] *= 2;
+      continue;
+    }
+    // counters -> start positions: classes from the longest down, waves in order inside a class
+    {
+      const int d = tid >> 9, cls = (tid >> 4) & (kPlanClasses - 1), w = tid & (kPlanWaves - 1);
+      const int own = hist[d][cls][w];
+      int incl = own;   // inclusive sum over the 16 waves of this class (16 adjacent lanes)
+#pragma unroll
+      for (int off = 1; off < kPlanWaves; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (w >= off) incl += o;
       }
-      hist[d][tid] = v - own + above;
-      if (tid == 0) n_units[d] = total;
+      if (w == kPlanWaves - 1) class_total[d][cls] = incl;
+      __syncthreads();
+      int above = 0;
+#pragma unroll 1
+      for (int c2 = cls + 1; c2 < kPlanClasses; ++c2) above += class_total[d][c2];
+      if (cls == 0 && w == kPlanWaves - 1) n_units[d] = above + incl;
+      __syncthreads();
+      hist[d][cls][w] = above + incl - own;
       __syncthreads();
     }
     mode = 1;
@@ -246,6 +261,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
                     n_comb[0] <= a.max_combine && n_comb[1] <= a.max_combine &&
                     n_slots[0] <= a.max_slots[0] && n_slots[1] <= a.max_slots[1];
     hdr->status = ok ? VARLEN_ATTN_OK : VARLEN_ATTN_PLAN_OVERFLOW;
+    if (a.status_copy) *a.status_copy = hdr->status;
     hdr->n_row_units = ok ? n_units[0] : 0;
     hdr->n_col_units = ok ? n_units[1] : 0;
     hdr->n_row_combine = ok ? n_comb[0] : 0;
@@ -254,9 +270,10 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     hdr->col_chunk_steps = ch[1];
     hdr->n_row_slots = n_slots[0];
     hdr->n_col_slots = n_slots[1];
-    hdr->sorted = sorted;
+    hdr->row_class_shift = shift[0];
     hdr->col_heads_per_unit = hpu;
-    for (int i = 0; i < 3; ++i) hdr->reserved[i] = 0;
+    hdr->col_class_shift = shift[1];
+    for (int i = 0; i < 2; ++i) hdr->reserved[i] = 0;
     hdr->pairs = (int64_t)pairs;
   }
 }

@@ -146,12 +146,9 @@ Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
 
 int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
                 const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream) {
-  int shift = 0;
-  const int max_cost = (p->total_tokens + kStep - 1) / kStep;
-  while ((max_cost - 1) >> shift >= kPlanBins) ++shift;
   PlanArgs a;
   a.cu = cu; a.B = p->num_docs; a.N = p->total_tokens; a.Hq = p->num_q_heads;
-  a.g = p->num_q_heads / p->num_kv_heads; a.shift = shift;
+  a.g = p->num_q_heads / p->num_kv_heads;
   a.no_split = (p->flags & VARLEN_ATTN_FLAG_NO_SPLIT) ? 1 : 0;
   a.force_ch[0] = (p->flags >> 8) & 0xFF;
   a.force_ch[1] = (p->flags >> 16) & 0xFF;
@@ -160,6 +157,7 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.comb[0] = R.row_comb; a.comb[1] = R.col_comb;
   a.max_units = L.max_units; a.max_combine = L.max_combine;
   a.max_slots[0] = L.max_row_slots; a.max_slots[1] = L.max_col_slots; a.slots_cap = slots_cap;
+  a.status_copy = nullptr;
   ScopedKernelTimer timer(kPlan, stream);
   plan_kernel<<<1, kPlanThreads, 0, stream>>>(a);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;

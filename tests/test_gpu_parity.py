@@ -63,7 +63,7 @@ def test_small_shapes_full_parity(gpu, lengths, hq, hkv, d):
     w = W.custom("small", lengths, hq, hkv, d, seed=sum(lengths) + 13 * hq + d)
     prob = run_all(gpu, w)
     errs = assert_close_full(prob.results(), oracle_full(w), label=str(lengths[:6]))
-    print("  errors (E1, E2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
+    print("  errors (E1, row-wise):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
 
 
 def test_non_default_scale_and_std(gpu):
@@ -83,7 +83,11 @@ def test_extreme_logit_ranges(gpu, std, d):
     got = prob.results()
     for name in ("o", "lse", "dq", "dk", "dv"):
         assert np.isfinite(got[name]).all(), name
-    assert_close_full(got, oracle_full(w), f"std {std}")
+    # The backward reads O as the forward stored it (bf16), so its D = rowsum(dO * O) carries
+    # 2^-9 of sum |dO O|; with values four times larger that is 16 times the usual absolute
+    # error, spread over dQ rows that are tiny where a row is one-hot: the row-wise gate is
+    # widened for this case, the tensor-scale gates are not.
+    assert_close_full(got, oracle_full(w), f"std {std}", row_tol_scale=4.0)
 
 
 def test_config1_tiny_full(gpu):
@@ -143,7 +147,7 @@ def test_config3_longtail_full(gpu):
     w = W.config(3)
     prob = run_all(gpu, w)
     errs = assert_close_full(prob.results(), oracle_full(w), "cfg3")
-    print("cfg3 errors (E1, E2):", errs, flush=True)
+    print("cfg3 errors (E1, row-wise):", errs, flush=True)
 
 
 def test_config4_gqa_full(gpu):
@@ -151,7 +155,7 @@ def test_config4_gqa_full(gpu):
     w = W.config(4)
     prob = run_all(gpu, w)
     errs = assert_close_full(prob.results(), oracle_full(w), "cfg4")
-    print("cfg4 errors (E1, E2):", errs, flush=True)
+    print("cfg4 errors (E1, row-wise):", errs, flush=True)
 
 
 def test_config3_and_4_sampled_rows_and_properties(gpu):
@@ -172,7 +176,7 @@ def test_config5_sweep_microbatches_full(gpu, first):
         for k, (a, b) in errs.items():
             worst[k] = (max(worst.get(k, (0, 0))[0], a), max(worst.get(k, (0, 0))[1], b))
         del prob
-    print(f"cfg5 microbatches {first}..{first + 15} worst (E1, E2):", worst, flush=True)
+    print(f"cfg5 microbatches {first}..{first + 15} worst (E1, row-wise):", worst, flush=True)
 
 
 def test_mid_size_long_document_full(gpu):
@@ -192,11 +196,11 @@ def _check_plan(prob, w, no_split):
     g = w.n_q_heads // w.n_kv_heads
     assert hdr.status == 0 and hdr.pairs == oplan.pairs(cu) == w.pairs
     assert hdr.col_heads_per_unit >= 1 and g % hdr.col_heads_per_unit == 0
-    for units, comb, chains, n_slots, always_slots in (
+    for units, comb, chains, n_slots, always_slots, shift in (
             (plan["row_units"], plan["row_combine"], oplan.row_chain_steps(cu, 128, 64),
-             hdr.n_row_slots, False),
+             hdr.n_row_slots, False, hdr.row_class_shift),
             (plan["col_units"], plan["col_combine"], oplan.col_chain_steps(cu, 128, 64),
-             hdr.n_col_slots, g > hdr.col_heads_per_unit)):
+             hdr.n_col_slots, g > hdr.col_heads_per_unit, hdr.col_class_shift)):
         assert len(units) <= L.max_units and len(comb) <= L.max_combine
         by_tile = {}
         for r0, s, e, b0, b1, slot, cost, _ in units.tolist():
@@ -222,8 +226,8 @@ def _check_plan(prob, w, no_split):
             else:
                 assert chunks[0][2] == -1 and (key[0], key[2]) not in comb_map
         assert sorted(used_slots) == list(range(n_slots)), "slots must be dense and disjoint"
-        if hdr.sorted:
-            assert (np.diff(units[:, 6]) <= 0).all(), "units must be ordered longest job first"
+        assert 0 <= shift < 31 and ((int(units[:, 6].max()) - 1) >> shift) < 32
+        assert (np.diff((units[:, 6] - 1) >> shift) <= 0).all(), "units must be ordered longest class first"
     return plan
 
 
@@ -238,7 +242,7 @@ def test_plan_integers_match_oracle(gpu, k, no_split):
     hdr = plan["header"]
     print(f"cfg{k} no_split={no_split}: row units {hdr.n_row_units} (chunk {hdr.row_chunk_steps}), "
           f"col units {hdr.n_col_units} (chunk {hdr.col_chunk_steps}), slots {hdr.n_row_slots}/"
-          f"{hdr.n_col_slots}, sorted {hdr.sorted}", flush=True)
+          f"{hdr.n_col_slots}, class shifts {hdr.row_class_shift}/{hdr.col_class_shift}", flush=True)
 
 
 def test_plan_many_short_documents(gpu):
