@@ -63,6 +63,13 @@ extern "C" {
                                                  than the workspace holds; no work was planned and
                                                  no output is written */
 
+#define VARLEN_ATTN_STATIC_TOO_LARGE (-7)      /* varlen_attn_fwd_static only: the problem needs more
+                                                 than VARLEN_ATTN_STATIC_SCRATCH_BYTES of workspace */
+
+/* Size of the workspace that the library itself holds on every GPU it runs on, for
+ * varlen_attn_fwd_static. */
+#define VARLEN_ATTN_STATIC_SCRATCH_BYTES (40u << 20)
+
 /* flags */
 #define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* bwd only: the workspace still holds the plan that a
                                          preceding varlen_attn_fwd / varlen_attn_plan call
@@ -177,6 +184,25 @@ int varlen_attn_plan(const varlen_attn_params* params, const int32_t* cu_seqlens
 int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void* k,
                     const void* v, const int32_t* cu_seqlens, void* o, float* lse,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* varlen_attn_fwd for callers that can neither allocate nor provide a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * arguments and results (bit for bit) as varlen_attn_fwd, but the workspace is a fixed array of
+ * VARLEN_ATTN_STATIC_SCRATCH_BYTES (40 MiB) of device memory inside the library, one copy per
+ * GPU, held until the process ends.  The call allocates and frees nothing (its first call on a
+ * device looks the array's address up).  A problem whose forward workspace (plan, D / LSE area
+ * and row partial results: about 33 - 35 MiB for 4 q heads at head_dim 128, whatever N) exceeds
+ * the array is refused with VARLEN_ATTN_STATIC_TOO_LARGE before any device work.
+ * plan_status: optional DEVICE int32 (4-byte aligned), or NULL; the plan step writes its status
+ * word there as well (VARLEN_ATTN_OK, _BAD_CU_SEQLENS, _PLAN_OVERFLOW), since the caller has no
+ * workspace to pass to varlen_attn_check.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two host threads) race; serialise them.  Nothing in the array needs to start at
+ * zero: every call rewrites the plan and every partial result it reads.  The plan is not kept
+ * for a later varlen_attn_bwd (which plans into its own workspace). */
+int varlen_attn_fwd_static(const varlen_attn_params* params, const void* q, const void* k,
+                           const void* v, const int32_t* cu_seqlens, void* o, float* lse,
+                           int32_t* plan_status, void* hip_stream);
 
 /* Backward of the same operation (the B chunk of the schedule DAG of Section 5.2; its cost is
  * the quadratic term of Eq. 1 as well).  With P_tj = exp(S_tj - lse_t), D_t = sum_c dO_tc O_tc:

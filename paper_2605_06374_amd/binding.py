@@ -24,6 +24,8 @@ WORKSPACE_TOO_SMALL = -3
 LAUNCH_FAILED = -4
 BAD_CU_SEQLENS = -5
 PLAN_OVERFLOW = -6
+STATIC_TOO_LARGE = -7
+STATIC_SCRATCH_BYTES = 40 << 20
 FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
 
@@ -102,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.varlen_attn_plan.argtypes = [pp, vp, vp, sz, vp]
         L.varlen_attn_fwd.restype = ctypes.c_int
         L.varlen_attn_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.varlen_attn_fwd_static.restype = ctypes.c_int
+        L.varlen_attn_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.varlen_attn_bwd.restype = ctypes.c_int
         L.varlen_attn_bwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.varlen_attn_check.restype = ctypes.c_int
@@ -185,6 +189,12 @@ def varlen_attn_fwd(params, q, k, v, cu_seqlens, o, lse, workspace, workspace_by
     return int(lib().varlen_attn_fwd(ctypes.byref(params), _addr(q), _addr(k), _addr(v),
                                      _addr(cu_seqlens), _addr(o), _addr(lse), _addr(workspace),
                                      _nbytes(workspace, workspace_bytes), _stream(stream)))
+
+
+def varlen_attn_fwd_static(params, q, k, v, cu_seqlens, o, lse, plan_status=None, stream=None) -> int:
+    return int(lib().varlen_attn_fwd_static(ctypes.byref(params), _addr(q), _addr(k), _addr(v),
+                                            _addr(cu_seqlens), _addr(o), _addr(lse),
+                                            _addr(plan_status), _stream(stream)))
 
 
 def varlen_attn_bwd(params, q, k, v, o, lse, d_o, cu_seqlens, dq, dk, dv, workspace,

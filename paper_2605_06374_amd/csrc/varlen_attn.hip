@@ -72,6 +72,39 @@ struct ScopedKernelTimer {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+}  // namespace
+
+// ----------------------------------------------------------------------------------------
+// Workspace of varlen_attn_fwd_static: device memory that belongs to the library, so that the
+// call needs no workspace from the caller and allocates nothing.  Every GPU this library runs
+// on holds its own copy of the array, at its own address, until the process ends.  In host
+// code the name below is only a handle for hipGetSymbolAddress: the address that kernels and
+// copies use is the one that call returns for the current device, kept in StaticScratch.
+// ----------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[VARLEN_ATTN_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  std::mutex mu;
+  void* ptr[kMaxDevices] = {};
+};
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out) {
+  static StaticScratch st;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VARLEN_ATTN_LAUNCH_FAILED;
+  std::lock_guard<std::mutex> g(st.mu);
+  if (!st.ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return VARLEN_ATTN_LAUNCH_FAILED;
+    st.ptr[dev] = p;
+  }
+  *out = st.ptr[dev];
+  return VARLEN_ATTN_OK;
+}
+
 bool params_ok(const varlen_attn_params* p) {
   if (!p) return false;
   if (p->total_tokens < 1 || p->num_docs < 1 || p->num_q_heads < 1 || p->num_kv_heads < 1) return false;
@@ -145,7 +178,8 @@ Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
 }
 
 int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
-                const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream) {
+                const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream,
+                int32_t* status_copy = nullptr) {
   PlanArgs a;
   a.cu = cu; a.B = p->num_docs; a.N = p->total_tokens; a.Hq = p->num_q_heads;
   a.g = p->num_q_heads / p->num_kv_heads;
@@ -157,7 +191,7 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.comb[0] = R.row_comb; a.comb[1] = R.col_comb;
   a.max_units = L.max_units; a.max_combine = L.max_combine;
   a.max_slots[0] = L.max_row_slots; a.max_slots[1] = L.max_col_slots; a.slots_cap = slots_cap;
-  a.status_copy = nullptr;
+  a.status_copy = status_copy;
   ScopedKernelTimer timer(kPlan, stream);
   plan_kernel<<<1, kPlanThreads, 0, stream>>>(a);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
@@ -261,6 +295,35 @@ int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void*
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
+int varlen_attn_fwd_static(const varlen_attn_params* params, const void* q, const void* k,
+                           const void* v, const int32_t* cu_seqlens, void* o, float* lse,
+                           int32_t* plan_status, void* hip_stream) {
+  varlen_attn_workspace_layout L;
+  int cap;
+  void* ws = nullptr;
+  const void* ptrs[] = {q, k, v, cu_seqlens, o, lse};
+  // validate against a workspace of unlimited size first: bad arguments keep their own codes
+  if (!params_ok(params)) return VARLEN_ATTN_INVALID_ARG;
+  for (const void* ptr : ptrs)
+    if (!ptr) return VARLEN_ATTN_INVALID_ARG;
+  if (plan_status && (reinterpret_cast<uintptr_t>(plan_status) & 3)) return VARLEN_ATTN_UNSUPPORTED;
+  if (params->head_dim != 64 && params->head_dim != 128) return VARLEN_ATTN_UNSUPPORTED;
+  for (const void* ptr : ptrs)
+    if (!aligned16(ptr)) return VARLEN_ATTN_UNSUPPORTED;
+  if (!layout_of(params, &L, &cap)) return VARLEN_ATTN_UNSUPPORTED;
+  // the forward touches the workspace up to the end of the row partial results only
+  if (L.col_partials_offset > (size_t)VARLEN_ATTN_STATIC_SCRATCH_BYTES) return VARLEN_ATTN_STATIC_TOO_LARGE;
+  int rc = static_scratch(&ws);
+  if (rc != VARLEN_ATTN_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const Regions R = regions_of(static_cast<char*>(ws), L);
+  rc = launch_plan(params, cu_seqlens, R, L, cap, stream, plan_status);
+  if (rc != VARLEN_ATTN_OK) return rc;
+  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream);
+  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream);
+  return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
+}
+
 int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void* k, const void* v,
                     const void* o, const float* lse, const void* d_o, const int32_t* cu_seqlens,
                     void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
@@ -336,6 +399,7 @@ const char* varlen_attn_status_string(int status) {
     case VARLEN_ATTN_LAUNCH_FAILED: return "kernel launch failed";
     case VARLEN_ATTN_BAD_CU_SEQLENS: return "malformed cu_seqlens";
     case VARLEN_ATTN_PLAN_OVERFLOW: return "plan does not fit the workspace";
+    case VARLEN_ATTN_STATIC_TOO_LARGE: return "problem exceeds the library's static workspace";
     default: return "unknown status";
   }
 }
