@@ -79,6 +79,9 @@ extern "C" {
                                          (bit-identical results under repacking), at the
                                          price of idle compute units on short microbatches */
 
+#define VARLEN_ATTN_FLAG_PLAN_LARGE 8 /* testing: plan with the general (16-wave) form of the plan kernel
+                                         also where the single-wave form would be taken */
+
 /* Tuning: bits 8..15 of flags = longest chunk of a row chain, bits 16..23 = of a column chain,
  * in steps (0 = chosen by the plan from the microbatch; the plan still lengthens a value
  * whose partial results would not fit the workspace). */

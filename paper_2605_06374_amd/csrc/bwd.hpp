@@ -176,6 +176,62 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   if (row_valid) store_rows<D>(dq + ((size_t)my_row * Hq + head) * D, acc, h, scale);
 }
 
+// Sum of the dQ partials of one cut tile and q head by one whole workgroup (thread t owns the
+// float4s t, t + 256, ... of the fragment; chunks are added in chain order, as many loads in
+// flight as four chunks of four float4s).  These workgroups ride at the end of the dK/dV
+// kernel's grid: the dQ partials are complete when that kernel starts, and its last round
+// leaves most compute units idle, so the reduction costs no launch and no time of its own.
+template <int D>
+__device__ __forceinline__ void dq_tile_combine(int block, const varlen_attn_plan_header* __restrict__ hdr,
+                                                int max_items,
+                                                const varlen_attn_combine_item* __restrict__ items,
+                                                const float* __restrict__ partials,
+                                                __bf16* __restrict__ dq, int Hq, float scale) {
+  constexpr int DB = D / 32;
+  constexpr int kPerThread = kTile * D / 4 / kThreads;   // float4s of a fragment per thread
+  const int idx = block / Hq, head = block % Hq;
+  // both loads in flight together
+  const int n_items = hdr->n_row_combine;
+  const varlen_attn_combine_item it = items[min(idx, max_items - 1)];
+  if (idx >= n_items) return;
+  const size_t pstride = (size_t)Hq * frag_floats<D>();
+  const float* p0 = partials + ((size_t)it.slot0 * Hq + head) * frag_floats<D>() + (size_t)threadIdx.x * 4;
+#pragma unroll 1
+  for (int s0 = 0; s0 < kPerThread; s0 += 4) {
+    f32x4 acc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int c0 = 0; c0 < it.n_chunks; c0 += 4) {
+      f32x4 x[4][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          x[j][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (c0 + j < it.n_chunks)   // the same for the whole workgroup
+            x[j][u] = *reinterpret_cast<const f32x4*>(p0 + (size_t)(c0 + j) * pstride +
+                                                      (size_t)(s0 + u) * kThreads * 4);
+        }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (c0 + j < it.n_chunks) acc[u] += x[j][u];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = (s0 + u) * kThreads + threadIdx.x;
+      const int lane = t & 63, rq = (t >> 6) & 3, db = (t >> 8) % DB, wave = (t >> 8) / DB;
+      const int h = lane >> 5, c = lane & 31;
+      const int my_row = it.row0 + 32 * wave + c;
+      if (my_row < it.doc_end)
+        *reinterpret_cast<uint2*>(dq + ((size_t)my_row * Hq + head) * D + 32 * db + 8 * rq + 4 * h) =
+            pack4(acc[u][0] * scale, acc[u][1] * scale, acc[u][2] * scale, acc[u][3] * scale);
+    }
+  }
+}
+
 // ----------------------------------------------------------------------------------------
 // Backward, dK and dV.  One workgroup per (column unit, q head): wave w owns key rows
 // row0 + 32w .. +31, keeps their K and V fragments in registers, and sweeps the unit's
@@ -183,7 +239,7 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 //   S = Q K^T, dP = dO V^T (query rows in registers r, key on the lane),
 //   dV^T += dO^T P,  dK^T += Q^T dS.
 // With grouped-query attention, or when the chain is cut, the unit stores fp32 partials
-// [dK | dV] that sum_combine_kernel adds up over the chunks and the q heads of the group.
+// [dK | dV] that bwd_combine_kernel adds up over the chunks and the q heads of the group.
 // ----------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(kThreads, 1)
@@ -193,7 +249,9 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                const varlen_attn_plan_header* __restrict__ hdr,
                const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ dk,
                __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
-               float scale, int max_units) {
+               float scale, int max_units, int unit_blocks,
+               const varlen_attn_combine_item* __restrict__ row_items, int max_items,
+               const float* __restrict__ row_partials, __bf16* __restrict__ dq) {
   constexpr int KK = D / 16, DB = D / 32;
   // Two stages of kStep = 64 query rows: one stage of lookahead is a whole stage of compute
   // (this kernel runs one workgroup per CU), and 64 KB of tiles keeps every LDS offset inside
@@ -206,6 +264,11 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // Q stages | dO stages | per-wave stat copies
   __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes + NS * 4 * kStatBytes];
 
+  // the workgroups behind the units sum the dQ partials that the dQ kernel left
+  if ((int)blockIdx.x >= unit_blocks) {
+    dq_tile_combine<D>(blockIdx.x - unit_blocks, hdr, max_items, row_items, row_partials, dq, Hq, scale);
+    return;
+  }
   int unit_idx, head;
   decode_block(blockIdx.x, Hq, unit_idx, head);
   // both loads in flight together; the unit array always has max_units >= grid / Hq entries
@@ -497,22 +560,16 @@ __device__ __forceinline__ void sum_combine(int block, int n_items,
       pack4(acc[0] * mul, acc[1] * mul, acc[2] * mul, acc[3] * mul);
 }
 
-// One launch for both backward reductions: the first `dkv_blocks` workgroups sum the
-// [dK | dV] partials (over chunks and the q heads of a group), the rest sum the dQ partials.
+// The [dK | dV] reduction (over chunks and the q heads of a group); the dQ partials are summed
+// at the end of the dK/dV kernel's grid.
 template <int D>
 __global__ void __launch_bounds__(kThreads)
 bwd_combine_kernel(const varlen_attn_plan_header* __restrict__ hdr,
                    const varlen_attn_combine_item* __restrict__ col_items,
-                   const varlen_attn_combine_item* __restrict__ row_items,
-                   const float* __restrict__ col_partials, const float* __restrict__ row_partials,
-                   __bf16* __restrict__ dk, __bf16* __restrict__ dv, __bf16* __restrict__ dq,
-                   int Hq, int Hkv, float scale, int dkv_blocks) {
-  if ((int)blockIdx.x < dkv_blocks)
-    sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale,
-                      hdr->col_heads_per_unit);
-  else
-    sum_combine<D, 1>(blockIdx.x - dkv_blocks, hdr->n_row_combine, row_items, row_partials, dq, nullptr,
-                      Hq, 1, scale);
+                   const float* __restrict__ col_partials, __bf16* __restrict__ dk,
+                   __bf16* __restrict__ dv, int Hq, int Hkv, float scale) {
+  sum_combine<D, 2>(blockIdx.x, hdr->n_col_combine, col_items, col_partials, dk, dv, Hq, Hq / Hkv, scale,
+                    hdr->col_heads_per_unit);
 }
 
 }  // namespace

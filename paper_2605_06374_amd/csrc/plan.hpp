@@ -27,8 +27,8 @@ namespace {
 // the same-address atomics of a wave stay inside the wave, and two sweeps over the tiles
 // (count, then place) that run the same code.
 // ----------------------------------------------------------------------------------------
-constexpr int kPlanThreads = 1024;
-constexpr int kPlanWaves = kPlanThreads / 64;
+constexpr int kPlanThreadsLarge = 1024;   // general form
+constexpr int kPlanThreadsSmall = 64;     // one wave: every barrier is free, nothing is shared between waves
 constexpr int kPlanClasses = 32;
 constexpr int kMinChunkSteps = 4;
 constexpr int kResidentGroups = 512;  // 256 CUs x 2 workgroups (forward, dQ)
@@ -58,7 +58,10 @@ __device__ __forceinline__ int wave_inclusive_sum(int v, int lane) {
   return v;
 }
 
+template <int kPlanThreads>
 __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
+  constexpr int kPlanWaves = kPlanThreads / 64;
+  static_assert(2 * kPlanClasses * kPlanWaves == kPlanThreads, "one thread per class counter");
   __shared__ int doc_first_tile[kPlanThreads + 1];  // running tile count of the batch's documents
   __shared__ int doc_s[kPlanThreads], doc_e[kPlanThreads];
   __shared__ int hist[2][kPlanClasses][kPlanWaves];    // units per (direction, class, wave), then cursors
@@ -151,7 +154,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         shift[d] = 0;
         while ((min(ch[d], longest) - 1) >> shift[d] >= kPlanClasses) ++shift[d];
       }
-      reinterpret_cast<int*>(hist)[tid] = 0;   // 2 x 32 x 16 = 1024 counters
+      reinterpret_cast<int*>(hist)[tid] = 0;   // 2 x 32 x waves counters: one per thread
       if (tid < 2) split[tid] = 0;
       __syncthreads();
     }
@@ -233,7 +236,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     }
     // counters -> start positions: classes from the longest down, waves in order inside a class
     {
-      const int d = tid >> 9, cls = (tid >> 4) & (kPlanClasses - 1), w = tid & (kPlanWaves - 1);
+      const int d = tid / (kPlanClasses * kPlanWaves), cls = (tid / kPlanWaves) % kPlanClasses,
+                w = tid % kPlanWaves;
       const int own = hist[d][cls][w];
       int incl = own;   // inclusive sum over the 16 waves of this class (16 adjacent lanes)
 #pragma unroll

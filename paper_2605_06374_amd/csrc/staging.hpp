@@ -135,14 +135,17 @@ __device__ __forceinline__ bf16x8 read_trans(const char* stage, const FragOffset
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Decode the id so
-// that all units of one head land on the same XCDs and share its K/V (or Q/dO) lines in L2.
+// that all units of one head land on the same XCDs and share its K/V (or Q/dO) lines in L2;
+// where a head has several XCDs, runs of kUnitRun consecutive units stay on one of them: the
+// chunks of one tile are neighbours in the unit list and read the same Q (dO, O; K, V) rows.
+constexpr int kUnitRun = 4;
 __device__ __forceinline__ void decode_block(int bid, int Hq, int& unit, int& head) {
   constexpr int kXcds = 8;
   const int xcd = bid % kXcds, local = bid / kXcds;
   if (kXcds % Hq == 0) {
     const int per = kXcds / Hq;          // XCDs per head
     head = xcd % Hq;
-    unit = local * per + xcd / Hq;
+    unit = (local / kUnitRun) * (kUnitRun * per) + (xcd / Hq) * kUnitRun + local % kUnitRun;
   } else if (Hq % kXcds == 0) {
     const int per = Hq / kXcds;          // heads per XCD
     head = xcd + kXcds * (local % per);
@@ -152,7 +155,11 @@ __device__ __forceinline__ void decode_block(int bid, int Hq, int& unit, int& he
     head = bid % Hq;
   }
 }
-inline unsigned grid_for(int units, int Hq) { return (unsigned)(((long long)units * Hq + 7) / 8 * 8); }
+// grid that covers `units` units of every head under decode_block (whole runs on every XCD)
+inline unsigned grid_for(int units, int Hq) {
+  const long long round = 8 * kUnitRun;
+  return (unsigned)(((long long)units * Hq + round - 1) / round * round);
+}
 
 }  // namespace
 

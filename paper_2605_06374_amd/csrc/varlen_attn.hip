@@ -193,7 +193,11 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.max_slots[0] = L.max_row_slots; a.max_slots[1] = L.max_col_slots; a.slots_cap = slots_cap;
   a.status_copy = status_copy;
   ScopedKernelTimer timer(kPlan, stream);
-  plan_kernel<<<1, kPlanThreads, 0, stream>>>(a);
+  // a microbatch with few documents and tiles is planned by a single wave (lower latency)
+  const long long tiles = (long long)p->total_tokens / kTile + p->num_docs;
+  const bool small = !(p->flags & VARLEN_ATTN_FLAG_PLAN_LARGE) && p->num_docs <= 2 * kPlanThreadsSmall && tiles <= 4 * kPlanThreadsSmall;
+  if (small) plan_kernel<kPlanThreadsSmall><<<1, kPlanThreadsSmall, 0, stream>>>(a);
+  else plan_kernel<kPlanThreadsLarge><<<1, kPlanThreadsLarge, 0, stream>>>(a);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
@@ -210,7 +214,8 @@ void launch_fwd(const varlen_attn_params* p, const void* q, const void* k, const
   }
   if (!(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT)) {
     ScopedKernelTimer timer(kFwdCombine, stream);
-    fwd_combine_kernel<D><<<dim3((unsigned)L.max_combine * Hq * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
+    const int cut_tiles = std::max(1, std::min(L.max_combine, L.max_row_slots / 2));   // see launch_bwd
+    fwd_combine_kernel<D><<<dim3((unsigned)cut_tiles * Hq * (kTile * D / 4 / kThreads)), kThreads, 0, stream>>>(
         R.hdr, R.row_comb, R.row_part, (__bf16*)o, lse, N, Hq);
   }
 }
@@ -230,21 +235,27 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
         lse, R.dsum, lse2, R.hdr, R.row_units, (__bf16*)dq, R.row_part, N, Hq, Hkv, scale,
         L.max_units);
   }
-  {
-    ScopedKernelTimer timer(kDkv, stream);
-    bwd_dkv_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse2, R.dsum, R.hdr,
-        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale, L.max_units);
-  }
   const bool split = !(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT);
+  // A cut chain has at least two chunks and all chunks of cut chains fit the slots, so at most
+  // max_row_slots / 2 tiles are cut in either direction.
+  const int cut_tiles = std::max(1, std::min(L.max_combine, L.max_row_slots / 2));
+  {
+    // behind its units: one workgroup per (cut tile, q head) that sums the dQ partials
+    const unsigned unit_blocks = grid_for(L.max_units, Hq);
+    const unsigned dq_blocks = split ? (unsigned)cut_tiles * Hq : 0u;
+    ScopedKernelTimer timer(kDkv, stream);
+    bwd_dkv_kernel<D><<<dim3(unit_blocks + dq_blocks), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse2, R.dsum, R.hdr,
+        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale, L.max_units,
+        (int)unit_blocks, R.row_comb, L.max_combine, R.row_part, (__bf16*)dq);
+  }
   if (split || Hq != Hkv) {
     constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;
-    const int dkv_blocks = L.max_combine * Hkv * 2 * kBlocksPerItem;   // bounded by layout_of
-    const int dq_blocks = split ? L.max_combine * Hq * kBlocksPerItem : 0;
+    // grouped-query attention: every tile's [dK | dV] is summed over the group; else cut tiles only
+    const int col_items = Hq != Hkv ? L.max_combine : cut_tiles;
     ScopedKernelTimer timer(kBwdCombine, stream);
-    bwd_combine_kernel<D><<<dim3((unsigned)(dkv_blocks + dq_blocks)), kThreads, 0, stream>>>(
-        R.hdr, R.col_comb, R.row_comb, R.col_part, R.row_part, (__bf16*)dk, (__bf16*)dv, (__bf16*)dq,
-        Hq, Hkv, scale, dkv_blocks);
+    bwd_combine_kernel<D><<<dim3((unsigned)(col_items * Hkv * 2 * kBlocksPerItem)), kThreads, 0, stream>>>(
+        R.hdr, R.col_comb, R.col_part, (__bf16*)dk, (__bf16*)dv, Hq, Hkv, scale);
   }
 }
 
