@@ -333,62 +333,32 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 #pragma unroll
   for (int i = 0; i < DB; ++i) { dkacc[i] = f32x16(0.f); dvacc[i] = f32x16(0.f); }
 
-  // One 32-query block of a stage against this wave's 32 keys.  MASKED: the block may touch
-  // the diagonal or run past the document end (queries there are clamped duplicates).
-  auto block = [&](const char* qt, const char* dot, const char* st, int qb, int q0, auto masked_c) {
-    constexpr bool MASKED = decltype(masked_c)::value;
-    const int qb0 = q0 + 32 * qb;
-    if (MASKED && (qb0 + 31 < wave_kv0 || qb0 >= it.doc_end)) return;  // wave-uniform
-    f32x16 s = f32x16(0.f), dp = f32x16(0.f);
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      s = mfma(lds_read_frag(qt, fo.row_frag[kk] + qb * 32 * D * 2), kf[kk], s);
-      dp = mfma(lds_read_frag(dot, fo.row_frag[kk] + qb * 32 * D * 2), vf[kk], dp);
-    }
-    f32x16 p;
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      const int rel = 32 * qb + 8 * rq + 4 * h;
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + rel * 4);
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 256 + rel * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 4 * rq + e;
-        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cs, -l4[e]));
-        if (MASKED) {
-          const int t = q0 + rel + e;
-          if (t < my_kv || t >= it.doc_end) pv = 0.f;
-        }
-        p[r] = pv;
-        s[r] = pv * (dp[r] - d4[e]);
-      }
-    }
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-      const bf16x8 pb = pack8(p, 8 * cc);
-      const bf16x8 dsb = pack8(s, 8 * cc);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        dvacc[db] = mfma(read_trans<D>(dot + qb * 32 * D * 2, fo, cc, db), pb, dvacc[db]);
-        dkacc[db] = mfma(read_trans<D>(qt + qb * 32 * D * 2, fo, cc, db), dsb, dkacc[db]);
-      }
-    }
-  };
-  // A whole 64-query stage away from the diagonal and the document end: the two 32-query
-  // blocks are software-pipelined by hand (this kernel runs one wave per SIMD, so nothing
-  // else hides LDS latency or overlaps the exponentials with the matrix pipe):
+  // A 64-query stage against this wave's 32 keys: the two 32-query blocks are software-pipelined
+  // by hand (this kernel runs one wave per SIMD, so nothing else hides LDS latency or overlaps
+  // the exponentials with the matrix pipe):
   //   R0 | M1(0) + R1 | V(0) with M1(1) + T0 | M2(0) with V(1) + T1 | M2(1)
   // R: row-fragment and statistics reads, T: transposed-fragment reads, M1: S and dP,
   // V: P and dS on the vector ALU, M2: dV and dK.  Each matrix instruction is written next to
   // the vector and LDS work that should ride on it, and the fences keep that order.
-  auto stage_fast = [&](const char* qt, const char* dot, const char* st) {
+  // MASKED: the stage touches the diagonal or runs past the document end (queries there are
+  // clamped duplicates): P of a (query, key) pair outside the mask is set to exactly 0.
+  auto stage = [&](const char* qt, const char* dot, const char* st, int q0, auto masked_c)
+      __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     constexpr int EPM = 16 / (2 * KK);  // score elements handled beside each matrix instruction
     bf16x8 qa[KK], da[KK], qb[KK], db_[KK];
     bf16x8 tq0[2][DB], td0[2][DB], tq1[2][DB], td1[2][DB];
     f32x4 l0[4], d0[4], l1[4], d1[4];
     // softmax of element r of one block: p = 2^(s cs - lse2), ds = p (dp - D)
-    auto soft = [&](f32x16& sv, const f32x16& dpv, f32x16& pv, const f32x4* l, const f32x4* dd, int r) {
-      const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], cs, -l[r >> 2][r & 3]));
+    // (r stands for query q0 + 32 qb + 8 (r / 4) + 4 h + r % 4)
+    const int t_lo = my_kv - q0 - 4 * h, t_hi = it.doc_end - q0 - 4 * h;   // allowed: t_lo <= 32 qb + 8 (r / 4) + r % 4 < t_hi
+    auto soft = [&](f32x16& sv, const f32x16& dpv, f32x16& pv, const f32x4* l, const f32x4* dd, int r, int qb)
+        __attribute__((always_inline)) {
+      float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], cs, -l[r >> 2][r & 3]));
+      if (MASKED) {
+        const int t = 32 * qb + 8 * (r >> 2) + (r & 3);
+        if (t < t_lo || t >= t_hi) e = 0.f;
+      }
       pv[r] = e;
       sv[r] = e * (dpv[r] - dd[r >> 2][r & 3]);
     };
@@ -424,12 +394,12 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       constexpr int kk = decltype(kk_c)::value;
       s1 = mfma(qb[kk], kf[kk], s1);
 #pragma unroll
-      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * 2 * kk + e);
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * 2 * kk + e, 0);
       td0[kk / DB][kk % DB] = read_trans<D>(dot, fo, kk / DB, kk % DB);
       __builtin_amdgcn_sched_barrier(0);
       dp1 = mfma(db_[kk], vf[kk], dp1);
 #pragma unroll
-      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * (2 * kk + 1) + e);
+      for (int e = 0; e < EPM; ++e) soft(s0, dp0, p0, l0, d0, EPM * (2 * kk + 1) + e, 0);
       tq0[kk / DB][kk % DB] = read_trans<D>(qt, fo, kk / DB, kk % DB);
       if ((kk + 1) * 2 * EPM % 8 == 0) {
         constexpr int i = (kk + 1) * 2 * EPM / 8 - 1;
@@ -445,12 +415,12 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       constexpr int j = decltype(j_c)::value;
       dvacc[j % DB] = mfma(td0[j / DB][j % DB], pb0[j / DB], dvacc[j % DB]);
 #pragma unroll
-      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * 2 * j + e);
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * 2 * j + e, 1);
       td1[j / DB][j % DB] = read_trans<D>(dot + 32 * D * 2, fo, j / DB, j % DB);
       __builtin_amdgcn_sched_barrier(0);
       dkacc[j % DB] = mfma(tq0[j / DB][j % DB], dsb0[j / DB], dkacc[j % DB]);
 #pragma unroll
-      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * (2 * j + 1) + e);
+      for (int e = 0; e < EPM; ++e) soft(s1, dp1, p1, l1, d1, EPM * (2 * j + 1) + e, 1);
       tq1[j / DB][j % DB] = read_trans<D>(qt + 32 * D * 2, fo, j / DB, j % DB);
       if ((j + 1) * 2 * EPM % 8 == 0) {
         constexpr int i = (j + 1) * 2 * EPM / 8 - 1;
@@ -479,12 +449,9 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     const char* qt = smem + ST * kStageBytes;
     const char* dot = smem + (NS + ST) * kStageBytes;
     const char* stt = stat_base + ST * 4 * kStatBytes;
-    if (step < 2 || q0 + kStep > it.doc_end) {
-      block(qt, dot, stt, 0, q0, std::true_type{});
-      block(qt, dot, stt, 1, q0, std::true_type{});
-    } else {
-      stage_fast(qt, dot, stt);
-    }
+    if (q0 + kStep - 1 < wave_kv0) return;   // every query of the stage lies before this wave's keys
+    if (q0 < wave_kv0 + 32 || q0 + kStep > it.doc_end) stage(qt, dot, stt, q0, std::true_type{});
+    else stage(qt, dot, stt, q0, std::false_type{});
   };
   for (;;) {
 #pragma unroll
