@@ -22,15 +22,33 @@ if ROOT not in sys.path:
 METRIC = "fwd+bwd causal attention TFLOP/s and % of bf16 MFMA peak per packed microbatch"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+CALIBRATION_COPY_BYTES = 256 << 20   # --calibrate-copy: bench_copy_kernel reads and writes this much
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the plain
-# device copy of --calibrate-copy (profiles/kernel_stats_and_counters_cfg2_7b_tp8_8k.md);
-# None for a (workload, kernel) pair that was not measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg2_7b_tp8_8k", "bwd_dkv_kernel"): 85.4e6,
-    ("cfg2_7b_tp8_8k", "bwd_dq_kernel"): 101.8e6,
-    ("cfg2_7b_tp8_8k", "fwd_kernel"): 73.3e6,
-}
+def csrc_digest() -> str:
+    """sha256 over the kernel sources: the key under which measured HBM traffic is kept."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2605_06374_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch (read + written) from profiles/hbm_traffic.json: rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE runs, scaled by a plain device copy of known size run under the
+    same command (the table is written by `python -m paper_2605_06374_amd.traffic_table`).
+    None when the kernel sources changed since the counters were read, or nothing was measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if table.get("csrc_sha256") != csrc_digest():
+        return None
+    e = table.get("entries", {}).get(workload, {}).get(kernel)
+    return None if e is None else float(e["fetch_bytes"] + e["write_bytes"])
 
 
 def main() -> int:
@@ -45,7 +63,7 @@ def main() -> int:
                     help="buffer sets rotated through (4 x 109 MB exceeds the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy 4 times, so that rocprofv3 --pmc "
+                    help="also run a plain 256 MiB device copy kernel 4 times, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -55,6 +73,10 @@ def main() -> int:
                     help="also time a pure bf16 MFMA kernel with constant and with hashed operands "
                          "(what the matrix pipe sustains on this box) and the LDS fragment reads "
                          "of the kernels alone; reported under mfma_rate")
+    ap.add_argument("--batched", type=int, default=0, metavar="K",
+                    help="K draws of the configuration (seed offsets 0, 100, ...) packed into ONE "
+                         "call of K times the tokens, against K separate calls: the several "
+                         "micro-batches per iteration of Table 3; prints one JSON line, then exits")
     ap.add_argument("--sweep", action="store_true",
                     help="length-skew sweep: time each of the 64 microbatches of configuration 5 "
                          "alone and fit T = c0 + beta * sum l(l+1)/2 (Eq. 1 at fixed N); prints a "
@@ -77,12 +99,14 @@ def main() -> int:
 
     if args.sweep:
         return sweep(args)
+    if args.batched:
+        return batched(args)
 
     if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        src = torch.empty(CALIBRATION_COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(4):
-            dst.copy_(src)
+            binding.varlen_attn_bench_copy(src, dst, CALIBRATION_COPY_BYTES)
         torch.cuda.synchronize()
         del src, dst
 
@@ -136,7 +160,7 @@ def main() -> int:
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "traffic": measured_traffic(w.name, dom),
                     "algorithmic_flops_per_launch": alg,
                     "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
 
@@ -160,6 +184,15 @@ def main() -> int:
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - g0) / args.steps * 1e3
 
+    # what the matrix pipe sustains on this machine right now (constant operands: clock; hashed
+    # operands: clock under the power draw of real data), beside the nominal 2.5 PFLOP/s
+    scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
+    sustained = {"unit": "TFLOP/s",
+                 "mfma_constant_operands": round(binding.varlen_attn_bench_mfma_rate(False, 4000, scratch.data_ptr()), 1),
+                 "mfma_hashed_operands": round(binding.varlen_attn_bench_mfma_rate(True, 4000, scratch.data_ptr()), 1)}
+    # 256 CUs x 4 SIMDs x 1024 flop per clock
+    sustained["implied_clock_mhz_constant_operands"] = round(
+        sustained["mfma_constant_operands"] * 1e12 / (torch.cuda.get_device_properties(0).multi_processor_count * 4096) / 1e6)
     mfma_rate = None
     if args.mfma_rate:
         scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
@@ -191,6 +224,14 @@ def main() -> int:
         cpu = {"value": round(flops * reps / total / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
                "kind": "oracle", "seconds": round(total, 2),
                "sample": f"whole {w.name} microbatch, forward + backward, {reps} times"}
+        if args.config in (1, 2):   # one thread as well (a few seconds on these two sizes)
+            oracle.set_threads(1)
+            c1 = time.perf_counter()
+            once()
+            one = time.perf_counter() - c1
+            oracle.set_threads(threads)
+            cpu["one_thread"] = {"value": round(flops / one / 1e12, 6), "unit": "TFLOP/s",
+                                 "seconds": round(one, 2), "sample": f"whole {w.name} microbatch once"}
 
     props = torch.cuda.get_device_properties(0)
     out = {
@@ -215,6 +256,9 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in kernels.items()},
+        "kernels_avg_us_note": "second pass with every launch bracketed by HIP events: a few percent "
+                               "above the undisturbed durations (rocprofv3 table under profiles/)",
+        "sustained": sustained,
         "fwd_bwd_tflops": split_tflops,
         "seed": w.seed,
         "device": {"name": props.name, "cus": props.multi_processor_count},
@@ -224,6 +268,67 @@ def main() -> int:
     if graph_ms is not None:
         out["graph_ms_per_step"] = round(graph_ms, 5)
     print(json.dumps(out))
+    return 0
+
+
+def batched(args) -> int:
+    """K micro-batches in one call.  Table 3 runs 4 to 8 micro-batches per iteration; the library
+    takes any packed cu_seqlens, so K micro-batches of one iteration can be handed over as one
+    K-times longer pack: fixed costs (plan, launches, reductions) are paid once."""
+    import numpy as np
+    import torch
+    from paper_2605_06374_amd import binding, workloads as W
+    from paper_2605_06374_amd.runner import DeviceProblem
+
+    k = args.batched
+    parts = [W.config(args.config, seed_offset=100 * i) for i in range(k)]
+    vals = [p.values() for p in parts]
+    lengths = [l for p in parts for l in p.lengths]
+    w0 = parts[0]
+    big = W.custom(f"{w0.name}_x{k}", lengths, w0.n_q_heads, w0.n_kv_heads, w0.head_dim, std=w0.std, seed=w0.seed)
+    big_vals = {n: np.concatenate([v[n] for v in vals], axis=0) for n in vals[0]}
+    flops = sum(p.flops_fwd_bwd for p in parts)
+    assert big.flops_fwd_bwd == flops
+
+    def timed(step, n_sets):
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps
+
+    # one call on the pack (buffer sets rotated as in the main benchmark)
+    n_sets = max(1, args.buffers)
+    packs = [DeviceProblem(big, values=big_vals) for _ in range(n_sets)]
+
+    def one_call(i):
+        p = packs[i % n_sets]
+        p.forward()
+        p.backward(reuse_plan=True)
+
+    t_one = timed(one_call, n_sets)
+    for p in packs:
+        assert binding.varlen_attn_check(p.workspace) == binding.OK
+    del packs
+    # K calls, one per micro-batch
+    sets = [[DeviceProblem(p, values=v) for p, v in zip(parts, vals)] for _ in range(n_sets)]
+
+    def k_calls(i):
+        for p in sets[i % n_sets]:
+            p.forward()
+            p.backward(reuse_plan=True)
+
+    t_k = timed(k_calls, n_sets)
+    print(json.dumps({"batched": big.name, "microbatches": k, "tokens": big.n_tokens, "docs": len(lengths),
+                      "pairs": big.pairs, "flops": flops, "steps": args.steps,
+                      "one_call": {"ms": round(t_one * 1e3, 5), "tflops": round(flops / t_one / 1e12, 1),
+                                   "frac_of_bf16_peak": round(flops / t_one / 1e12 / PEAK_BF16_TFLOPS, 4)},
+                      "separate_calls": {"ms": round(t_k * 1e3, 5), "tflops": round(flops / t_k / 1e12, 1),
+                                         "frac_of_bf16_peak": round(flops / t_k / 1e12 / PEAK_BF16_TFLOPS, 4)},
+                      "speedup": round(t_k / t_one, 3)}))
     return 0
 
 

@@ -53,6 +53,12 @@ int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* devic
 int varlen_attn_bench_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
                          float* bytes_per_clock_per_cu);
 
+/* Measurement aid: copies `bytes` (a multiple of 16; both DEVICE pointers 16-byte aligned) with a
+ * plain kernel named bench_copy_kernel, enqueued on `hip_stream`: reads `bytes` and writes `bytes`
+ * of HBM, the known quantity that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 run are
+ * scaled by. */
+int varlen_attn_bench_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -136,6 +136,8 @@ def bench_lib() -> ctypes.CDLL:
             getattr(L, name).restype = ctypes.c_int
             getattr(L, name).argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
                                          ctypes.POINTER(ctypes.c_float)]
+        L.varlen_attn_bench_copy.restype = ctypes.c_int
+        L.varlen_attn_bench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         _bench_lib = L
     return _bench_lib
 
@@ -237,6 +239,11 @@ def varlen_attn_bench_lds_rate(transposed: bool, iterations: int, device_scratch
                                      ctypes.c_void_p(int(device_scratch)),
                                      ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
     return float(out.value)
+
+
+def varlen_attn_bench_copy(src, dst, nbytes: int, stream=None) -> None:
+    """Plain device copy of known size (kernel bench_copy_kernel); see the bench header."""
+    check(bench_lib().varlen_attn_bench_copy(_addr(src), _addr(dst), int(nbytes), _stream(stream)))
 
 
 def varlen_attn_status_string(status: int) -> str:

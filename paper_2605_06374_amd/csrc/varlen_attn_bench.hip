@@ -10,7 +10,24 @@
 #include "staging.hpp"
 #include "mfma_rate.hpp"
 
+namespace {
+// plain copy of 16-byte words: a kernel of known HBM traffic, against which the FETCH_SIZE and
+// WRITE_SIZE counters of a profiler run are scaled
+__global__ void __launch_bounds__(256) bench_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+}  // namespace
+
 extern "C" {
+
+int varlen_attn_bench_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes < 16 || (bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) ||
+      (reinterpret_cast<uintptr_t>(dst) & 15))
+    return VARLEN_ATTN_INVALID_ARG;
+  bench_copy_kernel<<<dim3(2048), 256, 0, static_cast<hipStream_t>(hip_stream)>>>(
+      static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
+}
 
 int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* device_scratch,
                           void* hip_stream, float* tflops) {
