@@ -37,3 +37,21 @@ def decide(progress, fail_stop, delta, next_pending, memory_feasible):
     if j is None or not memory_feasible[d_max]:
         return None
     return d_min, d_max, j
+
+
+def decide_literal(progress, fail_stop, delta, next_pending, memory_feasible):
+    """The listing of Algorithm 1 taken literally: argmin and argmax over ALL groups (ties to the
+    lowest index), the test "(d_min, i) is fail-stop or the gap exceeds delta", NextPending of
+    d_min, MemoryFeasible of d_max.  Kept beside `decide` so that the tests can show where the
+    recorded reading departs from the listing: a fail-stop group that is ahead of the others is
+    never d_min here, so its pending work would stay where it cannot run, and a fail-stop group
+    can be d_max, i.e. a destination."""
+    groups = range(len(progress))
+    d_min = min(groups, key=lambda d: (progress[d], d))
+    d_max = max(groups, key=lambda d: (progress[d], -d))
+    if not (fail_stop[d_min] or progress[d_max] - progress[d_min] > delta):
+        return None
+    j = next_pending[d_min]
+    if j is None or not memory_feasible[d_max] or d_min == d_max:
+        return None
+    return d_min, d_max, j

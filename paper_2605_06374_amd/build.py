@@ -1,6 +1,7 @@
 """Compile csrc/varlen_attn.hip (with the .hpp files it includes) for gfx950 into libvarlen_attn.so,
 csrc/varlen_attn_bench.hip (measurement probes) into libvarlen_attn_bench.so, and the host-only
-csrc/mb_time.cpp, csrc/pipeline_dag.cpp, csrc/tp_select.cpp and csrc/migration_step.cpp into
+csrc/mb_time.cpp, csrc/pipeline_dag.cpp, csrc/tp_select.cpp, csrc/migration_step.cpp and
+csrc/migration_plan.cpp into
 shared libraries of the same names, next to this file."""
 from __future__ import annotations
 
@@ -34,15 +35,16 @@ FLAGS = [
 # host-only libraries: the Detector's predictors of Section 5.2, the Scheduler's TP subgroup
 # selection of Section 6.1 and migration decision of Section 6.3
 HOST_LIBS = {"libmb_time.so": "mb_time.cpp", "libpipeline_dag.so": "pipeline_dag.cpp",
-             "libtp_select.so": "tp_select.cpp", "libmigration_step.so": "migration_step.cpp"}
+             "libtp_select.so": "tp_select.cpp", "libmigration_step.so": "migration_step.cpp",
+             "libmigration_plan.so": "migration_plan.cpp migration_step.cpp"}
 
 
 def build_host(verbose: bool = False) -> list:
     out = []
     for lib, src in HOST_LIBS.items():
         cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-I" + os.path.join(ROOT, "include"), "-o", os.path.join(HERE, lib),
-               os.path.join(HERE, "csrc", src)]
+               "-I" + os.path.join(ROOT, "include"), "-o", os.path.join(HERE, lib)] + \
+              [os.path.join(HERE, "csrc", f) for f in src.split()]
         if verbose:
             print(" ".join(cmd))
         subprocess.run(cmd, check=True)

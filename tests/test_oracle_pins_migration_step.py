@@ -26,3 +26,27 @@ def test_no_self_migration_and_no_pending():
     assert O.decide([2, 2, 2], [False] * 3, 0, [1, 2, 3], [True] * 3) is None
     assert O.decide([5, 1], [False, False], 0, [None, None], [True, True]) is None
     assert O.decide([4], [False], 0, [9], [True]) is None
+
+
+def test_reading_against_the_literal_listing():
+    """The recorded reading (a fail-stop stage is never a destination, and is the source while it
+    has pending work) against the listing taken literally (argmin / argmax over all groups):
+    identical on every state without fail-stop stages, and on the fail-stop states the literal
+    form either agrees or shows the two defects the reading avoids."""
+    import itertools
+    for n in (2, 3):
+        for progress in itertools.product(range(3), repeat=n):
+            for pend in itertools.product((None, 7), repeat=n):
+                for mem in itertools.product((False, True), repeat=n):
+                    for delta in (0, 1):
+                        a = O.decide(list(progress), [False] * n, delta, list(pend), list(mem))
+                        b = O.decide_literal(list(progress), [False] * n, delta, list(pend), list(mem))
+                        assert a == b
+    # the paper's own example is the same under both
+    assert O.decide_literal([2, 1, 2], [False] * 3, 0, [None, 5, None], [True] * 3) == (1, 0, 5)
+    # defect 1: a crashed stage that happens to be ahead is never d_min, its work stays put
+    assert O.decide_literal([1, 5, 1], [False, True, False], 9, [None, 4, None], [True] * 3) is None
+    assert O.decide([1, 5, 1], [False, True, False], 9, [None, 4, None], [True] * 3) == (1, 0, 4)
+    # defect 2: a crashed stage with the largest count is taken as the destination
+    assert O.decide_literal([0, 5, 1], [False, True, False], 0, [3, None, None], [True] * 3) == (0, 1, 3)
+    assert O.decide([0, 5, 1], [False, True, False], 0, [3, None, None], [True] * 3) == (0, 2, 3)
