@@ -79,6 +79,17 @@ extern "C" {
                                          (bit-identical results under repacking), at the
                                          price of idle compute units on short microbatches */
 
+#define VARLEN_ATTN_FLAG_FUSED_BWD 16 /* bwd: one kernel for dQ, dK and dV, so that S and dP are
+                                         computed once for the whole backward (5 contractions per
+                                         (query, key) pair instead of the 7 of the two-kernel
+                                         form).  dQ is summed with floating-point atomics into an
+                                         fp32 array in the workspace and rounded afterwards: its
+                                         bits are NOT reproducible from run to run (dK, dV stay
+                                         reproducible).  The flag enlarges the workspace by
+                                         4 N Hq d bytes: pass it to varlen_attn_workspace_bytes and
+                                         to the forward call as well.  On MI355X this form is the
+                                         slower one (the atomic adds bound it) and exists for
+                                         comparison. */
 #define VARLEN_ATTN_FLAG_PLAN_LARGE 8 /* testing: plan with the general (16-wave) form of the plan kernel
                                          also where the single-wave form would be taken */
 
@@ -152,6 +163,8 @@ typedef struct {
   size_t dsum_offset;         /* fp32 D = rowsum(dO * O) [Hq, N], then LSE * log2(e) [Hq, N] */
   size_t row_partials_offset; /* fp32 partial results of cut row chains */
   size_t col_partials_offset; /* fp32 partial results of cut / grouped column chains */
+  size_t dq_accumulator_offset; /* fp32 dQ accumulator [N, Hq, d]; present (non-empty) only with
+                                   VARLEN_ATTN_FLAG_FUSED_BWD */
   size_t total_bytes;
   int32_t max_units;          /* capacity of each unit array */
   int32_t max_combine;        /* capacity of each combine array */
@@ -214,7 +227,8 @@ int varlen_attn_fwd_static(const varlen_attn_params* params, const void* q, cons
  * (dK, dV also summed over the q heads of a group).  Reads q, k, v, o, lse (as written by the
  * forward) and d_o; dq [N, Hq, d], dk, dv [N, Hkv, d] bf16 are fully overwritten.  Workspace and
  * status as for varlen_attn_fwd.
- * Deterministic: no atomics on floating-point data, results are bit-reproducible. */
+ * Deterministic: no atomics on floating-point data, results are bit-reproducible (unless
+ * VARLEN_ATTN_FLAG_FUSED_BWD asks for the single-kernel form). */
 int varlen_attn_bwd(const varlen_attn_params* params, const void* q, const void* k,
                     const void* v, const void* o, const float* lse, const void* d_o,
                     const int32_t* cu_seqlens, void* dq, void* dk, void* dv, void* workspace,

@@ -28,6 +28,8 @@ STATIC_TOO_LARGE = -7
 STATIC_SCRATCH_BYTES = 40 << 20
 FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
+FLAG_PLAN_LARGE = 8
+FLAG_FUSED_BWD = 16
 
 
 def flag_group_heads(n: int) -> int:
@@ -74,7 +76,8 @@ class WorkspaceLayout(ctypes.Structure):
     _fields_ = [("row_units_offset", ctypes.c_size_t), ("col_units_offset", ctypes.c_size_t),
                 ("row_combine_offset", ctypes.c_size_t), ("col_combine_offset", ctypes.c_size_t),
                 ("dsum_offset", ctypes.c_size_t), ("row_partials_offset", ctypes.c_size_t),
-                ("col_partials_offset", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t),
+                ("col_partials_offset", ctypes.c_size_t), ("dq_accumulator_offset", ctypes.c_size_t),
+                ("total_bytes", ctypes.c_size_t),
                 ("max_units", ctypes.c_int32), ("max_combine", ctypes.c_int32),
                 ("max_row_slots", ctypes.c_int32), ("max_col_slots", ctypes.c_int32)]
 

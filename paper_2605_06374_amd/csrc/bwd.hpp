@@ -176,6 +176,54 @@ bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   if (row_valid) store_rows<D>(dq + ((size_t)my_row * Hq + head) * D, acc, h, scale);
 }
 
+// ----------------------------------------------------------------------------------------
+// Fused backward (VARLEN_ATTN_FLAG_FUSED_BWD), first kernel: D = rowsum(dO * O) and
+// LSE * log2(e) for every (token, q head) into the workspace, and the fp32 dQ accumulator
+// cleared.  One group of D / 8 lanes per row (16 bytes per lane); HBM-bound.
+// ----------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+bwd_prep_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o,
+                const float* __restrict__ lse, float* __restrict__ dsum,
+                float* __restrict__ lse2_out, float* __restrict__ dq_acc, int N, int Hq) {
+  constexpr int kLanesPerRow = D / 8;
+  constexpr int kRowsPerBlock = kThreads / kLanesPerRow;
+  const long long row = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / kLanesPerRow;  // t * Hq + h
+  const int part = threadIdx.x % kLanesPerRow;
+  const bool valid = row < (long long)N * Hq;
+  float acc = 0.f;
+  if (valid) {
+    const uint4 a = *reinterpret_cast<const uint4*>(d_o + row * D + 8 * part);
+    const uint4 b = *reinterpret_cast<const uint4*>(o + row * D + 8 * part);
+    const bf16x8 x = __builtin_bit_cast(bf16x8, a), y = __builtin_bit_cast(bf16x8, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)x[e] * (float)y[e];
+    f32x4* z = reinterpret_cast<f32x4*>(dq_acc + row * D + 8 * part);
+    z[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    z[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int off = kLanesPerRow / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+  if (part == 0 && valid) {
+    const int t = (int)(row / Hq), h = (int)(row % Hq);
+    dsum[(size_t)h * N + t] = acc;
+    lse2_out[(size_t)h * N + t] = lse[(size_t)h * N + t] * kLog2e;
+  }
+}
+
+// Fused backward, last kernel: dQ = scale * accumulator, rounded to bf16.
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+bwd_dq_finish_kernel(const float* __restrict__ dq_acc, __bf16* __restrict__ dq, long long n8,
+                     float scale) {
+  const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;   // group of 8 elements
+  if (i >= n8) return;
+  const f32x4 a = reinterpret_cast<const f32x4*>(dq_acc)[2 * i], b = reinterpret_cast<const f32x4*>(dq_acc)[2 * i + 1];
+  const uint2 lo = pack4(a[0] * scale, a[1] * scale, a[2] * scale, a[3] * scale);
+  const uint2 hi = pack4(b[0] * scale, b[1] * scale, b[2] * scale, b[3] * scale);
+  reinterpret_cast<uint4*>(dq)[i] = uint4{lo.x, lo.y, hi.x, hi.y};
+}
+
 // Sum of the dQ partials of one cut tile and q head by one whole workgroup (thread t owns the
 // float4s t, t + 256, ... of the fragment; chunks are added in chain order, as many loads in
 // flight as four chunks of four float4s).  These workgroups ride at the end of the dK/dV
@@ -240,8 +288,15 @@ __device__ __forceinline__ void dq_tile_combine(int block, const varlen_attn_pla
 //   dV^T += dO^T P,  dK^T += Q^T dS.
 // With grouped-query attention, or when the chain is cut, the unit stores fp32 partials
 // [dK | dV] that bwd_combine_kernel adds up over the chunks and the q heads of the group.
+//
+// FUSED (VARLEN_ATTN_FLAG_FUSED_BWD): the kernel also forms dQ, so that S and dP are computed
+// once for the whole backward (5 contractions instead of 7).  dS of a stage goes, as bf16, into
+// an LDS tile [128 keys][64 queries]; one stage later wave w multiplies it with columns
+// 32w .. 32w+31 of the unit's K tile (kept in LDS for this) and adds the 64 x 32 block of
+// dQ = dS K into a fp32 accumulator in the workspace with floating-point atomics: the order of
+// those additions is not fixed, so dQ is not bit-reproducible in this mode.
 // ----------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool FUSED>
 __global__ void __launch_bounds__(kThreads, 1)
 bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                const __bf16* __restrict__ v, const __bf16* __restrict__ d_o,
@@ -251,7 +306,8 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                __bf16* __restrict__ dv, float* __restrict__ partials, int N, int Hq, int Hkv,
                float scale, int max_units, int unit_blocks,
                const varlen_attn_combine_item* __restrict__ row_items, int max_items,
-               const float* __restrict__ row_partials, __bf16* __restrict__ dq) {
+               const float* __restrict__ row_partials, __bf16* __restrict__ dq,
+               float* __restrict__ dq_acc) {
   constexpr int KK = D / 16, DB = D / 32;
   // Two stages of kStep = 64 query rows: one stage of lookahead is a whole stage of compute
   // (this kernel runs one workgroup per CU), and 64 KB of tiles keeps every LDS offset inside
@@ -261,11 +317,16 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   constexpr int kStatBytes = 512;             // lse2[64] then dsum[64], one copy per wave
   using Loader = StageLoader<D, kStep>;
   constexpr int LPS = 2 * Loader::kPerWave + 2;
-  // Q stages | dO stages | per-wave stat copies
-  __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes + NS * 4 * kStatBytes];
+  constexpr int kPlainBytes = 2 * NS * kStageBytes + NS * 4 * kStatBytes;
+  constexpr int kKeyTileBytes = FUSED ? kTile * D * 2 : 0;      // the unit's K rows [128][D]
+  constexpr int kDsBytes = FUSED ? kTile * kStep * 2 : 0;       // dS of a stage [128 keys][64 queries]
+  // Q stages | dO stages | per-wave stat copies | (fused: K tile | two dS tiles)
+  __shared__ __attribute__((aligned(1024))) char smem[kPlainBytes + kKeyTileBytes + 2 * kDsBytes];
+  char* const key_tile = smem + kPlainBytes;
+  char* const ds_tiles = key_tile + kKeyTileBytes;
 
   // the workgroups behind the units sum the dQ partials that the dQ kernel left
-  if ((int)blockIdx.x >= unit_blocks) {
+  if (!FUSED && (int)blockIdx.x >= unit_blocks) {
     dq_tile_combine<D>(blockIdx.x - unit_blocks, hdr, max_items, row_items, row_partials, dq, Hq, scale);
     return;
   }
@@ -299,6 +360,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const __bf16* dobase = d_o + (size_t)head * D;
   const float* lse_h = lse2 + (size_t)head * N;
   const float* dsum_h = dsum + (size_t)head * N;
+  float* dq_acc_h = FUSED ? dq_acc + (size_t)head * D : nullptr;
   int heads_left = hpu;
   const unsigned lds_q = lds_addr_of(smem), lds_do = lds_q + NS * kStageBytes;
   const unsigned lds_stat = lds_do + NS * kStageBytes + wave * kStatBytes;
@@ -327,7 +389,57 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   }
   FragOffsets<D> fo;
   fo.init(lane);
+  if (FUSED) {
+    StageLoader<D, kTile> key_loader;
+    key_loader.init(wave, lane, (unsigned)((size_t)Hkv * D * 2));
+    key_loader.issue(k + (size_t)kvh * D, it.row0, it.doc_end - 1, lds_addr_of(key_tile), wave);
+  }
   wait_all_vm_visible();
+  // this lane's row of the dS tiles: key 32 wave + c; element (key, query) sits in the 16-byte
+  // chunk query / 8 of that row, swizzled like every tile
+  // dS of one 32-query block, accumulator registers 8 cc .. 8 cc + 7 (queries 32 qb + 16 cc +
+  // 4h + {0..3} and + 8), into the dS tile
+  auto ds_store = [&](char* tile, const bf16x8& v, int qb, int cc) __attribute__((always_inline)) {
+    const uint4 w = __builtin_bit_cast(uint4, v);
+    const int ds_row_swz = swz<kStep>(32 * wave + c);     // recomputed: nothing extra stays live across a stage
+    char* row = tile + (32 * wave + c) * (kStep * 2) + 8 * h;
+    *reinterpret_cast<uint2*>(row + (((4 * qb + 2 * cc) ^ ds_row_swz) << 4)) = uint2{w.x, w.y};
+    *reinterpret_cast<uint2*>(row + (((4 * qb + 2 * cc + 1) ^ ds_row_swz) << 4)) = uint2{w.z, w.w};
+  };
+  // dQ of one finished stage: this wave's 32 columns of the head dimension, all 64 queries,
+  // summed over the key slices that hold a key some query of the stage may see
+  auto dq_flush = [&](const char* tile, int q0) __attribute__((always_inline)) {
+    const int keys = min(it.doc_end, q0 + kStep) - it.row0;
+    const int cc_end = min(max((keys + 15) / 16, 0), kTile / 16);
+    FragOffsets<kStep> fo_ds;      // the dS tile has rows of kStep elements
+    fo_ds.init(lane);
+    // the 2 x D / 32 blocks of 32 queries x 32 columns are dealt to the four waves
+    constexpr int kBlocks = DB / 2;                      // per wave: 2 (D = 128), 1 (D = 64)
+    const int db = DB == 4 ? wave : wave & 1;            // column block
+    const int qb0 = DB == 4 ? 0 : wave >> 1;             // first (only) query block
+    f32x16 acc[kBlocks];
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) acc[b] = f32x16(0.f);
+#pragma unroll 1
+    for (int cc = 0; cc < cc_end; ++cc) {
+      const bf16x8 kb = read_trans<D>(key_tile, fo, cc, db);
+#pragma unroll
+      for (int b = 0; b < kBlocks; ++b) {
+        // offsets of query block qb0 + b (selected, not indexed: the table stays in registers)
+        const int lo = (qb0 + b) ? fo_ds.trans[1][0] : fo_ds.trans[0][0];
+        const int hi = (qb0 + b) ? fo_ds.trans[1][1] : fo_ds.trans[0][1];
+        acc[b] = mfma(lds_read_tr8(tile + lo + cc * 16 * kStep * 2, tile + hi + cc * 16 * kStep * 2), kb, acc[b]);
+      }
+    }
+    float* col = dq_acc_h + 32 * db + c;
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = q0 + 32 * (qb0 + b) + 8 * (r / 4) + 4 * h + r % 4;
+        if (row < it.doc_end) unsafeAtomicAdd(col + (size_t)row * Hq * D, acc[b][r]);
+      }
+  };
 
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
@@ -342,7 +454,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // the vector and LDS work that should ride on it, and the fences keep that order.
   // MASKED: the stage touches the diagonal or runs past the document end (queries there are
   // clamped duplicates): P of a (query, key) pair outside the mask is set to exactly 0.
-  auto stage = [&](const char* qt, const char* dot, const char* st, int q0, auto masked_c)
+  auto stage = [&](const char* qt, const char* dot, const char* st, int q0, char* ds_tile, auto masked_c)
       __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;
     constexpr int EPM = 16 / (2 * KK);  // score elements handled beside each matrix instruction
@@ -405,6 +517,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         constexpr int i = (kk + 1) * 2 * EPM / 8 - 1;
         pb0[i] = pack8(p0, 8 * i);
         dsb0[i] = pack8(s0, 8 * i);
+        if (FUSED) ds_store(ds_tile, dsb0[i], 0, i);
       }
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -426,6 +539,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         constexpr int i = (j + 1) * 2 * EPM / 8 - 1;
         pb1[i] = pack8(p1, 8 * i);
         dsb1[i] = pack8(s1, 8 * i);
+        if (FUSED) ds_store(ds_tile, dsb1[i], 1, i);
       }
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -443,15 +557,18 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     wait_vm<(NS - 2) * LPS>();
     __syncthreads();
     issue(st + NS - 1, (ST + NS - 1) % NS);
-    if (!wave_active) return;
     const int step = it.step_begin + st;
     const int q0 = it.row0 + kStep * step;
+    // fused: dQ of the previous stage, whose dS every wave has written before the barrier above
+    if (FUSED && st > 0) dq_flush(ds_tiles + (1 - ST) * kDsBytes, q0 - kStep);
+    if (!wave_active) return;
     const char* qt = smem + ST * kStageBytes;
     const char* dot = smem + (NS + ST) * kStageBytes;
     const char* stt = stat_base + ST * 4 * kStatBytes;
     if (q0 + kStep - 1 < wave_kv0) return;   // every query of the stage lies before this wave's keys
-    if (q0 < wave_kv0 + 32 || q0 + kStep > it.doc_end) stage(qt, dot, stt, q0, std::true_type{});
-    else stage(qt, dot, stt, q0, std::false_type{});
+    char* ds_tile = ds_tiles + ST * kDsBytes;
+    if (q0 < wave_kv0 + 32 || q0 + kStep > it.doc_end) stage(qt, dot, stt, q0, ds_tile, std::true_type{});
+    else stage(qt, dot, stt, q0, ds_tile, std::false_type{});
   };
   for (;;) {
 #pragma unroll
@@ -462,9 +579,14 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
       body(st + 1, std::integral_constant<int, 1>{});
     }
     wait_vm<0>();  // nothing may still be landing in LDS when the workgroup goes on or retires
+    if (FUSED) {       // dQ of the chain's last stage
+      __syncthreads();
+      dq_flush(ds_tiles + ((n_steps - 1) & 1) * kDsBytes, it.row0 + kStep * (it.step_begin + n_steps - 1));
+    }
     if (--heads_left == 0) break;
     __syncthreads();   // every wave is done with the stages before they are refilled
     qbase += D; dobase += D; lse_h += N; dsum_h += N;
+    if (FUSED) dq_acc_h += D;
   }
 
   if (it.slot >= 0) {

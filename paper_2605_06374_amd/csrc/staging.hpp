@@ -134,6 +134,13 @@ __device__ __forceinline__ bf16x8 read_trans(const char* stage, const FragOffset
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// the same from two explicit addresses (rows .. and rows + 8 ..)
+__device__ __forceinline__ bf16x8 lds_read_tr8(const char* lo_addr, const char* hi_addr) {
+  bf16x4 lo = lds_read_tr(lo_addr);
+  bf16x4 hi = lds_read_tr(hi_addr);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Decode the id so
 // that all units of one head land on the same XCDs and share its K/V (or Q/dO) lines in L2;
 // where a head has several XCDs, runs of kUnitRun consecutive units stay on one of them: the

@@ -34,10 +34,10 @@ namespace {
 // ----------------------------------------------------------------------------------------
 // Optional per-kernel timing (host-side HIP events only; off by default).
 // ----------------------------------------------------------------------------------------
-enum KernelId { kPlan = 0, kFwd, kFwdCombine, kDq, kDkv, kBwdCombine, kNumKernels };
+enum KernelId { kPlan = 0, kFwd, kFwdCombine, kDq, kDkv, kBwdCombine, kPrep, kFusedBwd, kDqFinish, kNumKernels };
 const char* const kKernelNames[kNumKernels] = {
     "plan_kernel", "fwd_kernel", "fwd_combine_kernel", "bwd_dq_kernel", "bwd_dkv_kernel",
-    "bwd_combine_kernel"};
+    "bwd_combine_kernel", "bwd_prep_kernel", "bwd_fused_kernel", "bwd_dq_finish_kernel"};
 struct Profiler {
   std::mutex mu;
   bool enabled = false;
@@ -139,6 +139,10 @@ bool layout_of(const varlen_attn_params* p, varlen_attn_workspace_layout* L, int
   L->dsum_offset = off; off = align_up(off + 2 * sizeof(float) * (size_t)Hq * p->total_tokens, 256);
   L->row_partials_offset = off; off = align_up(off + fwd_part * Hq * L->max_row_slots, 256);
   L->col_partials_offset = off; off = align_up(off + 2 * frag * Hq * L->max_col_slots, 256);
+  // fused backward: fp32 dQ accumulator [N, Hq, d]
+  L->dq_accumulator_offset = off;
+  if (p->flags & VARLEN_ATTN_FLAG_FUSED_BWD)
+    off = align_up(off + sizeof(float) * (size_t)p->total_tokens * Hq * p->head_dim, 256);
   L->total_bytes = off;
   return true;
 }
@@ -164,7 +168,7 @@ struct Regions {
   varlen_attn_plan_header* hdr;
   varlen_attn_unit *row_units, *col_units;
   varlen_attn_combine_item *row_comb, *col_comb;
-  float *dsum, *row_part, *col_part;
+  float *dsum, *row_part, *col_part, *dq_acc;
 };
 Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
   return Regions{reinterpret_cast<varlen_attn_plan_header*>(ws),
@@ -174,7 +178,8 @@ Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
                  reinterpret_cast<varlen_attn_combine_item*>(ws + L.col_combine_offset),
                  reinterpret_cast<float*>(ws + L.dsum_offset),
                  reinterpret_cast<float*>(ws + L.row_partials_offset),
-                 reinterpret_cast<float*>(ws + L.col_partials_offset)};
+                 reinterpret_cast<float*>(ws + L.col_partials_offset),
+                 reinterpret_cast<float*>(ws + L.dq_accumulator_offset)};
 }
 
 int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
@@ -227,7 +232,15 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   const float scale = p->softmax_scale;
   float* lse2 = R.dsum + (size_t)Hq * N;
-  {
+  const bool fused = (p->flags & VARLEN_ATTN_FLAG_FUSED_BWD) != 0;
+  if (fused) {
+    // D = rowsum(dO * O), LSE * log2(e), and the dQ accumulator cleared
+    ScopedKernelTimer timer(kPrep, stream);
+    constexpr int kRowsPerBlock = kThreads / (D / 8);
+    const long long rows = (long long)N * Hq;
+    bwd_prep_kernel<D><<<dim3((unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock)), kThreads, 0, stream>>>(
+        (const __bf16*)o, (const __bf16*)d_o, lse, R.dsum, lse2, R.dq_acc, N, Hq);
+  } else {
     // also writes D = rowsum(dO * O) and LSE * log2(e), which the dK/dV kernel reads
     ScopedKernelTimer timer(kDq, stream);
     bwd_dq_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
@@ -239,15 +252,28 @@ void launch_bwd(const varlen_attn_params* p, const void* q, const void* k, const
   // A cut chain has at least two chunks and all chunks of cut chains fit the slots, so at most
   // max_row_slots / 2 tiles are cut in either direction.
   const int cut_tiles = std::max(1, std::min(L.max_combine, L.max_row_slots / 2));
-  {
-    // behind its units: one workgroup per (cut tile, q head) that sums the dQ partials
-    const unsigned unit_blocks = grid_for(L.max_units, Hq);
-    const unsigned dq_blocks = split ? (unsigned)cut_tiles * Hq : 0u;
-    ScopedKernelTimer timer(kDkv, stream);
-    bwd_dkv_kernel<D><<<dim3(unit_blocks + dq_blocks), kThreads, 0, stream>>>(
+  const unsigned unit_blocks = grid_for(L.max_units, Hq);
+  if (fused) {
+    // one kernel for dQ, dK and dV; dQ is summed in fp32 in the workspace and rounded afterwards
+    ScopedKernelTimer timer(kFusedBwd, stream);
+    bwd_dkv_kernel<D, true><<<dim3(unit_blocks), kThreads, 0, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse2, R.dsum, R.hdr,
         R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale, L.max_units,
-        (int)unit_blocks, R.row_comb, L.max_combine, R.row_part, (__bf16*)dq);
+        (int)unit_blocks, R.row_comb, L.max_combine, R.row_part, (__bf16*)dq, R.dq_acc);
+  } else {
+    // behind its units: one workgroup per (cut tile, q head) that sums the dQ partials
+    const unsigned dq_blocks = split ? (unsigned)cut_tiles * Hq : 0u;
+    ScopedKernelTimer timer(kDkv, stream);
+    bwd_dkv_kernel<D, false><<<dim3(unit_blocks + dq_blocks), kThreads, 0, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)d_o, lse2, R.dsum, R.hdr,
+        R.col_units, (__bf16*)dk, (__bf16*)dv, R.col_part, N, Hq, Hkv, scale, L.max_units,
+        (int)unit_blocks, R.row_comb, L.max_combine, R.row_part, (__bf16*)dq, nullptr);
+  }
+  if (fused) {
+    const long long n8 = (long long)N * Hq * D / 8;
+    ScopedKernelTimer timer(kDqFinish, stream);
+    bwd_dq_finish_kernel<D><<<dim3((unsigned)((n8 + kThreads - 1) / kThreads)), kThreads, 0, stream>>>(
+        R.dq_acc, (__bf16*)dq, n8, scale);
   }
   if (split || Hq != Hkv) {
     constexpr int kBlocksPerItem = kTile * D / 4 / kThreads;

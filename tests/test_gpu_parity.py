@@ -384,6 +384,36 @@ def test_grouped_query_column_units_sweeping_heads(gpu, heads):
         assert_close_full(prob.results(), oracle_full(w), f"gqa sweep {heads} {lengths}")
 
 
+@pytest.mark.parametrize("lengths,hq,hkv,d", SMALL + [([900, 130, 1500, 64, 1], 8, 2, 128)])
+def test_fused_backward_small_shapes(gpu, lengths, hq, hkv, d):
+    """The single-kernel backward (dQ by fp32 atomics): same oracle, same tolerances; dV is
+    computed by the same arithmetic as in the two-kernel form, hence bit-identical to it (dK is
+    not: D = rowsum(dO * O) is summed by another kernel, in another order)."""
+    from paper_2605_06374_amd import binding
+    print(f"fused case lengths={lengths[:8]} hq={hq} hkv={hkv} d={d}", flush=True)
+    w = W.custom("fused", lengths, hq, hkv, d, seed=sum(lengths) + 13 * hq + d)
+    prob = run_all(gpu, w, flags=binding.FLAG_FUSED_BWD)
+    assert_close_full(prob.results(), oracle_full(w), label="fused " + str(lengths[:6]))
+    base, got = run_all(gpu, w).result_bits(), prob.result_bits()
+    for n in ("o", "lse", "dv"):
+        assert np.array_equal(got[n], base[n]), n
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_fused_backward_configs(gpu, k):
+    from paper_2605_06374_amd import binding
+    w = W.config(k)
+    prob = run_all(gpu, w, flags=binding.FLAG_FUSED_BWD)
+    errs = assert_close_full(prob.results(), oracle_full(w), f"fused cfg{k}")
+    print(f"fused cfg{k} errors (E1, row-wise):", errs, flush=True)
+    # the workspace grows by the fp32 dQ accumulator only when the flag is given
+    L0 = binding.varlen_attn_workspace_regions(binding.make_params(w.n_tokens, len(w.lengths), w.n_q_heads,
+                                                                    w.n_kv_heads, w.head_dim, 0.1, 0))
+    L1 = binding.varlen_attn_workspace_regions(prob.params)
+    assert L1.total_bytes - L0.total_bytes >= 4 * w.n_tokens * w.n_q_heads * w.head_dim
+    assert L0.total_bytes == L0.dq_accumulator_offset
+
+
 def test_bit_reproducible(gpu):
     w = W.config(4)
     a = run_all(gpu, w).result_bits()
