@@ -368,12 +368,22 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 
   Loader loader;
   loader.init(wave, lane, (unsigned)((size_t)Hq * D * 2));
+  // stages are issued in order, one call per step: the wave-uniform addresses of the next
+  // stage's first Q and dO rows live in scalar registers and move on by one stage per call
+  const unsigned long long kStageStride = (unsigned long long)kStep * ((size_t)Hq * D * 2);
+  unsigned long long q_next = 0, do_next = 0;
+  auto restart = [&]() {   // at the first step of a chain (of every head the unit sweeps)
+    const size_t first = (size_t)(it.row0 + kStep * it.step_begin) * ((size_t)Hq * D * 2);
+    q_next = uniform64(reinterpret_cast<const char*>(qbase) + first);
+    do_next = uniform64(reinterpret_cast<const char*>(dobase) + first);
+  };
   auto issue = [&](int st, int stage) {
     const int q0 = it.row0 + kStep * (it.step_begin + min(st, n_steps - 1));
-    loader.issue(qbase, q0, it.doc_end - 1, lds_q + stage * kStageBytes, wave);
-    loader.issue(dobase, q0, it.doc_end - 1, lds_do + stage * kStageBytes, wave);
+    loader.issue_at(q_next, q0, it.doc_end - 1, lds_q + stage * kStageBytes, wave);
+    loader.issue_at(do_next, q0, it.doc_end - 1, lds_do + stage * kStageBytes, wave);
     dma_floats64(lse_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes, lane);
     dma_floats64(dsum_h, q0, it.doc_end - 1, lds_stat + stage * 4 * kStatBytes + 256, lane);
+    if (st < n_steps - 1) { q_next += kStageStride; do_next += kStageStride; }
   };
   bf16x8 kf[KK], vf[KK];
 #pragma unroll
@@ -571,6 +581,7 @@ bwd_dkv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     else stage(qt, dot, stt, q0, ds_tile, std::false_type{});
   };
   for (;;) {
+    restart();
 #pragma unroll
     for (int st = 0; st < NS - 1; ++st) issue(st, st);
     for (int st = 0; st < n_steps; st += NS) {
