@@ -24,14 +24,18 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 CALIBRATION_COPY_BYTES = 256 << 20   # --calibrate-copy: bench_copy_kernel reads and writes this much
 
+ATTENTION_SOURCES = ("varlen_attn.hip", "tiles.hpp", "staging.hpp", "fragments.hpp", "plan.hpp",
+                     "fwd.hpp", "bwd.hpp")
+
+
 def csrc_digest() -> str:
-    """sha256 over the kernel sources: the key under which measured HBM traffic is kept."""
-    import glob
+    """sha256 over the sources of the attention library: the key under which measured HBM
+    traffic is kept (the benchmarking aids and the host-only libraries are not part of it)."""
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2605_06374_amd", "csrc", "*.h*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in ATTENTION_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2605_06374_amd", "csrc", name), "rb").read())
     return h.hexdigest()
 
 
@@ -77,6 +81,13 @@ def main() -> int:
                     help="K draws of the configuration (seed offsets 0, 100, ...) packed into ONE "
                          "call of K times the tokens, against K separate calls: the several "
                          "micro-batches per iteration of Table 3; prints one JSON line, then exits")
+    ap.add_argument("--fused-bwd", action="store_true",
+                    help="run the backward as the single-kernel variant (dQ accumulated with fp32 "
+                         "atomic adds) instead of the default two-kernel form")
+    ap.add_argument("--atomic-rate", action="store_true",
+                    help="time fp32 atomic adds in the access pattern of the single-kernel backward "
+                         "(a 64 x 128 block of dQ per workgroup and stage) against plain stores of "
+                         "the same pattern; prints one JSON line, then exits")
     ap.add_argument("--sweep", action="store_true",
                     help="length-skew sweep: time each of the 64 microbatches of configuration 5 "
                          "alone and fit T = c0 + beta * sum l(l+1)/2 (Eq. 1 at fixed N); prints a "
@@ -101,6 +112,17 @@ def main() -> int:
         return sweep(args)
     if args.batched:
         return batched(args)
+    if args.atomic_rate:
+        buf = torch.zeros(128 << 20, dtype=torch.uint8, device="cuda:0")
+        rows = {}
+        for name, mode, regions, stride in (("atomic_private_region_per_workgroup", 0, 256, 0),
+                                            ("atomic_one_region_shared_by_all", 0, 1, 0),
+                                            ("atomic_sweep_over_16MB", 0, 512, 1),
+                                            ("store_sweep_over_16MB", 1, 512, 1)):
+            rows[name] = round(binding.varlen_attn_bench_atomic_rate(mode, 64, regions, stride, buf), 1)
+        print(json.dumps({"atomic_rate": rows, "unit": "GB/s of 4-byte adds (stores)", "workgroups": 256,
+                          "bytes_per_workgroup_and_stage": 32768}))
+        return 0
 
     if args.calibrate_copy:
         src = torch.empty(CALIBRATION_COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -112,7 +134,8 @@ def main() -> int:
 
     w = W.config(args.config, seed_offset=args.seed_offset)
     vals = w.values()
-    probs = [DeviceProblem(w, values=vals) for _ in range(max(1, args.buffers))]
+    flags = binding.FLAG_FUSED_BWD if args.fused_bwd else 0
+    probs = [DeviceProblem(w, values=vals, flags=flags) for _ in range(max(1, args.buffers))]
 
     def step(i):
         p = probs[i % len(probs)]
@@ -150,10 +173,12 @@ def main() -> int:
         # forward alone (with its plan) and backward alone, by the same FLOP convention
         split_tflops = {
             "fwd": round(4 * pair_flops / (us("plan_kernel", "fwd_kernel", "fwd_combine_kernel") * 1e-6) / 1e12, 1),
-            "bwd": round(10 * pair_flops / (us("bwd_dq_kernel", "bwd_dkv_kernel", "bwd_combine_kernel") * 1e-6) / 1e12, 1)}
+            "bwd": round(10 * pair_flops / (us("bwd_dq_kernel", "bwd_dkv_kernel", "bwd_combine_kernel", "bwd_prep_kernel",
+                                               "bwd_fused_kernel", "bwd_dq_finish_kernel") * 1e-6) / 1e12, 1)}
         # algorithmic flops per launch: 2*d per (pair, contraction); forward S and PV;
         # dK/dV kernel S, dP, dV, dK; dQ kernel only the dQ contraction is new work
-        per_pair = {"fwd_kernel": 4, "bwd_dkv_kernel": 8, "bwd_dq_kernel": 2}
+        # (the single-kernel backward: all five)
+        per_pair = {"fwd_kernel": 4, "bwd_dkv_kernel": 8, "bwd_dq_kernel": 2, "bwd_fused_kernel": 10}
         dom = max((k for k in kernels if k in per_pair), key=lambda k: kernels[k]["avg_us"])
         alg = per_pair[dom] * w.head_dim * w.n_q_heads * w.pairs
         achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e12
@@ -250,7 +275,7 @@ def main() -> int:
         "config": {"workload": w.name, "tokens": w.n_tokens, "docs": len(w.lengths),
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "pairs": w.pairs, "flops_per_step": flops, "buffer_sets": len(probs),
-                   "step": "plan + fwd + bwd"},
+                   "step": "plan + fwd + bwd", "backward": "single kernel" if args.fused_bwd else "two kernels"},
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "algorithmic_GBps": round(w.algorithmic_bytes / sec_per_step / 1e9, 1),
         "roofline": roofline,

@@ -53,6 +53,15 @@ int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* devic
 int varlen_attn_bench_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
                          float* bytes_per_clock_per_cu);
 
+/* Measurement aid: fp32 atomic adds (mode 0) or plain stores (mode 1) in the access pattern of the
+ * single-kernel backward: 256 workgroups, each adding a block of 64 rows x 128 floats per stage,
+ * `stages` times; the block of workgroup b at stage s is region (b + s * stride) % regions of
+ * `device_buffer` (regions * 32 KiB <= buffer_bytes; the buffer's contents are overwritten).
+ * Runs twice on `hip_stream` and writes the rate of the second run, in GB/s of 4-byte values, to
+ * the HOST float.  Blocks the host. */
+int varlen_attn_bench_atomic_rate(int mode, int stages, int regions, int stride, void* device_buffer,
+                                  size_t buffer_bytes, void* hip_stream, float* gigabytes_per_second);
+
 /* Measurement aid: copies `bytes` (a multiple of 16; both DEVICE pointers 16-byte aligned) with a
  * plain kernel named bench_copy_kernel, enqueued on `hip_stream`: reads `bytes` and writes `bytes`
  * of HBM, the known quantity that the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 run are

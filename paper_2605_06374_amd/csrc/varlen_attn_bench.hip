@@ -16,9 +16,54 @@ namespace {
 __global__ void __launch_bounds__(256) bench_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
+// fp32 adds in the access pattern of the single-kernel backward: per stage a workgroup adds a
+// block of 64 rows x 128 floats (32 KB), wave w columns 32w .. 32w+31, lanes 0-31 one row and
+// lanes 32-63 the row four further (an accumulator tile).  mode 0: atomic adds, 1: plain stores.
+// The block of workgroup b at stage s is region (b + s * stride) % regions.
+__global__ void __launch_bounds__(256) bench_atomic_kernel(float* buf, int stages, int regions, int stride, int mode) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5, c = lane & 31;
+  for (int s = 0; s < stages; ++s) {
+    const size_t region = (size_t)(((long long)blockIdx.x + (long long)s * stride) % regions);
+    float* base = buf + region * 64 * 128 + 32 * wave + c;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float* p = base + (32 * qb + 8 * (r / 4) + 4 * h + r % 4) * 128;
+        if (mode == 0) unsafeAtomicAdd(p, 1.0f);
+        else *p = 1.0f;
+      }
+  }
+}
 }  // namespace
 
 extern "C" {
+
+int varlen_attn_bench_atomic_rate(int mode, int stages, int regions, int stride, void* device_buffer,
+                                  size_t buffer_bytes, void* hip_stream, float* gigabytes_per_second) {
+  if (!device_buffer || !gigabytes_per_second || stages < 1 || stages > (1 << 20) || regions < 1 ||
+      stride < 0 || (mode != 0 && mode != 1) || (size_t)regions * 32768 > buffer_bytes)
+    return VARLEN_ATTN_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return VARLEN_ATTN_LAUNCH_FAILED;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return VARLEN_ATTN_LAUNCH_FAILED; }
+  const unsigned grid = 256;
+  float ms = 0.f;
+  bool ok = true;
+  for (int pass = 0; pass < 2 && ok; ++pass) {   // the first pass warms up
+    ok = hipEventRecord(e0, stream) == hipSuccess;
+    bench_atomic_kernel<<<dim3(grid), 256, 0, stream>>>(static_cast<float*>(device_buffer), stages, regions,
+                                                        stride, mode);
+    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, stream) == hipSuccess &&
+         hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0.f) return VARLEN_ATTN_LAUNCH_FAILED;
+  *gigabytes_per_second = (float)((double)grid * stages * 32768.0 / (ms * 1e-3) / 1e9);
+  return VARLEN_ATTN_OK;
+}
 
 int varlen_attn_bench_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
   if (!src || !dst || bytes < 16 || (bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) ||
