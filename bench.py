@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--fused-bwd", action="store_true",
                     help="run the backward as the single-kernel variant (dQ accumulated with fp32 "
                          "atomic adds) instead of the default two-kernel form")
+    ap.add_argument("--overlap-probe", action="store_true",
+                    help="time matrix and vector instruction streams alone, side by side on one SIMD "
+                         "(two waves) and interleaved in one wave; prints one JSON line, then exits")
     ap.add_argument("--atomic-rate", action="store_true",
                     help="time fp32 atomic adds in the access pattern of the single-kernel backward "
                          "(a 64 x 128 block of dQ per workgroup and stage) against plain stores of "
@@ -112,6 +115,18 @@ def main() -> int:
         return sweep(args)
     if args.batched:
         return batched(args)
+    if args.overlap_probe:
+        scratch = torch.zeros(256, dtype=torch.float32, device="cuda:0")
+        cases = (("one wave per SIMD: 16 MFMA", 0, -1), ("one wave per SIMD: 64 fma", 1, -1),
+                 ("one wave per SIMD: 16 exp", 2, -1), ("two waves per SIMD: 16 MFMA each", 0, 0),
+                 ("two waves per SIMD: 64 fma each", 1, 1), ("two waves per SIMD: 16 exp each", 2, 2),
+                 ("two waves per SIMD: 16 MFMA | 64 fma", 0, 1), ("two waves per SIMD: 16 MFMA | 16 exp", 0, 2),
+                 ("one wave per SIMD: 16 x (MFMA, 4 fma)", 3, -1), ("one wave per SIMD: 16 x (MFMA, exp)", 4, -1),
+                 ("two waves per SIMD: 16 x (MFMA, 4 fma) each", 3, 3), ("two waves per SIMD: 16 x (MFMA, exp) each", 4, 4))
+        rows = {name: round(binding.varlen_attn_bench_overlap(a, b, 20000, scratch.data_ptr()), 1) for name, a, b in cases}
+        print(json.dumps({"overlap_probe": rows, "unit": "clocks of 2.4 GHz per iteration",
+                          "ideal_16_mfma": 512, "ideal_64_fma": 256, "ideal_16_exp": 256}))
+        return 0
     if args.atomic_rate:
         buf = torch.zeros(128 << 20, dtype=torch.uint8, device="cuda:0")
         rows = {}

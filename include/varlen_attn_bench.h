@@ -53,6 +53,17 @@ int varlen_attn_bench_mfma_rate(int random_operands, int iterations, void* devic
 int varlen_attn_bench_lds_rate(int transposed, int iterations, void* device_scratch, void* hip_stream,
                          float* bytes_per_clock_per_cu);
 
+/* Measurement aid: do matrix and vector instructions overlap on one SIMD?  One workgroup of
+ * eight waves per compute unit; waves 0-3 (one per SIMD) run work_a, waves 4-7 work_b.  Work per
+ * iteration: 0 = sixteen bf16 MFMA 32x32x16 on four accumulators; 1 = sixty-four independent
+ * fp32 fma; 2 = sixteen v_exp_f32; 3 = sixteen times (one MFMA, four fma) in one instruction
+ * stream; 4 = sixteen times (one MFMA, one exp); -1 = nothing.  Supported pairs: (w, -1) for
+ * every w, (0,0), (1,1), (2,2), (3,3), (4,4), (0,1), (0,2).  Runs twice on `hip_stream` and
+ * writes the second run's time per iteration, in clocks of the nominal 2.4 GHz, to the HOST
+ * float.  `device_scratch`: any 4 writable device bytes.  Blocks the host. */
+int varlen_attn_bench_overlap(int work_a, int work_b, int iterations, void* device_scratch,
+                              void* hip_stream, float* clocks_per_iteration);
+
 /* Measurement aid: fp32 atomic adds (mode 0) or plain stores (mode 1) in the access pattern of the
  * single-kernel backward: 256 workgroups, each adding a block of 64 rows x 128 floats per stage,
  * `stages` times; the block of workgroup b at stage s is region (b + s * stride) % regions of

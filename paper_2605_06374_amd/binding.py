@@ -139,6 +139,9 @@ def bench_lib() -> ctypes.CDLL:
             getattr(L, name).restype = ctypes.c_int
             getattr(L, name).argtypes = [ctypes.c_int, ctypes.c_int, vp, vp,
                                          ctypes.POINTER(ctypes.c_float)]
+        L.varlen_attn_bench_overlap.restype = ctypes.c_int
+        L.varlen_attn_bench_overlap.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp,
+                                                ctypes.POINTER(ctypes.c_float)]
         L.varlen_attn_bench_atomic_rate.restype = ctypes.c_int
         L.varlen_attn_bench_atomic_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                     vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float)]
@@ -244,6 +247,15 @@ def varlen_attn_bench_lds_rate(transposed: bool, iterations: int, device_scratch
     check(bench_lib().varlen_attn_bench_lds_rate(int(bool(transposed)), int(iterations),
                                      ctypes.c_void_p(int(device_scratch)),
                                      ctypes.c_void_p(int(stream or 0)), ctypes.byref(out)))
+    return float(out.value)
+
+
+def varlen_attn_bench_overlap(work_a: int, work_b: int, iterations: int, scratch_ptr: int, stream=None) -> float:
+    """Nominal clocks per iteration of the matrix / vector overlap probe; see the bench header."""
+    out = ctypes.c_float(0.0)
+    check(bench_lib().varlen_attn_bench_overlap(int(work_a), int(work_b), int(iterations),
+                                                ctypes.c_void_p(int(scratch_ptr)), _stream(stream),
+                                                ctypes.byref(out)))
     return float(out.value)
 
 
