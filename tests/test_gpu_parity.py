@@ -497,3 +497,27 @@ def test_mfma_rate_probe_runs(gpu):
     for transposed in (False, True):
         rate = binding.varlen_attn_bench_lds_rate(transposed, 2000, scratch.data_ptr())
         assert 16.0 < rate < 600.0, rate
+
+
+def test_overlap_and_atomic_probes_run(gpu):
+    """The other measurement aids return plausible figures and reject bad arguments."""
+    import torch
+    from paper_2605_06374_amd import binding
+    scratch = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    alone = binding.varlen_attn_bench_overlap(0, -1, 500, scratch.data_ptr())      # 16 MFMA: 512 clocks at full rate
+    assert 450.0 < alone < 3000.0, alone
+    both = binding.varlen_attn_bench_overlap(0, 1, 500, scratch.data_ptr())
+    assert alone * 0.8 < both < 3.0 * alone, (alone, both)
+    with pytest.raises(RuntimeError):
+        binding.varlen_attn_bench_overlap(1, 0, 500, scratch.data_ptr())            # not an offered pair
+    with pytest.raises(RuntimeError):
+        binding.varlen_attn_bench_overlap(0, -1, 0, scratch.data_ptr())
+    buf = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda:0")
+    for mode in (0, 1):
+        rate = binding.varlen_attn_bench_atomic_rate(mode, 8, 64, 1, buf)
+        assert 20.0 < rate < 20000.0, (mode, rate)
+    # block (b + s * stride) % regions of workgroup b: every one of the 64 regions gets adds
+    torch.cuda.synchronize()
+    assert float(buf.view(torch.float32)[: 64 * 64 * 128].min()) >= 1.0
+    with pytest.raises(RuntimeError):
+        binding.varlen_attn_bench_atomic_rate(0, 8, 1 << 20, 1, buf)                # regions do not fit the buffer
