@@ -1,10 +1,10 @@
 """Turns two rocprofv3 counter runs of bench.py (FETCH_SIZE, WRITE_SIZE) into the table of
 measured HBM bytes per launch that bench.py reports under roofline.traffic.
 
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o pmc -- \\
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d prof/pmc_fetch -o pmc -- \\
         python3 bench.py --steps 8 --warmup 2 --no-cpu-baseline --no-kernel-timing --calibrate-copy
-    (the same with WRITE_SIZE into gpurun_out/pmc_write)
-    python -m paper_2605_06374_amd.traffic_table <workload> gpurun_out/pmc_fetch gpurun_out/pmc_write
+    (the same with WRITE_SIZE into prof/pmc_write)
+    python -m paper_2605_06374_amd.traffic_table <workload> prof/pmc_fetch prof/pmc_write
 
 Every counter is scaled by what it reads for bench_copy_kernel, a plain copy of known size run
 by --calibrate-copy under the same command.  The table is keyed by a digest of the kernel
