@@ -44,7 +44,7 @@ def test_bench_header_symbols_are_exported_by_the_two_libraries():
 def test_status_strings():
     seen = set()
     for code in (B.OK, B.INVALID_ARG, B.UNSUPPORTED, B.WORKSPACE_TOO_SMALL, B.LAUNCH_FAILED,
-                 B.BAD_CU_SEQLENS, B.PLAN_OVERFLOW):
+                 B.BAD_CU_SEQLENS, B.PLAN_OVERFLOW, B.STATIC_TOO_LARGE):
         text = B.varlen_attn_status_string(code)
         assert text and text != "unknown status" and text not in seen
         seen.add(text)
@@ -115,16 +115,6 @@ def test_argument_errors_are_reported_on_the_host():
     assert L.varlen_attn_check(None, None) == B.INVALID_ARG
 
 
-def test_status_strings():
-    seen = set()
-    for code in (0, -1, -2, -3, -4, -5):
-        s = B.varlen_attn_status_string(code)
-        assert s and s != "unknown status"
-        seen.add(s)
-    assert len(seen) == 6
-    assert B.varlen_attn_status_string(-99) == "unknown status"
-
-
 # ------------------------------------------------------------------ capacities of the workspace
 def _adversarial_cu_lists():
     import numpy as np
@@ -172,3 +162,30 @@ def test_workspace_capacities_bound_every_plan(hq, hkv):
                 if 2 * steps <= ch * cap:
                     assert slots <= cap
             assert fitting >= 1 and sum(-(-x // max(lens)) for x in lens if x > max(lens)) == 0
+
+
+# ------------------------------------------------------------------ separation of product and checker
+def _sources(*roots, suffixes=(".py", ".h", ".hpp", ".hip", ".c", ".cpp")):
+    for root in roots:
+        for dirpath, _, names in os.walk(os.path.join(ROOT, root)):
+            for n in names:
+                if n.endswith(suffixes):
+                    yield os.path.join(dirpath, n)
+
+
+def test_product_and_oracle_do_not_reach_into_each_other():
+    """The package never imports, includes or loads anything of oracle/, and oracle/ nothing of the
+    package; only the tests, the smoke entry and the benchmark's baseline leg use the oracle."""
+    import re
+    for path in _sources("paper_2605_06374_amd", "include"):
+        text = open(path).read()
+        assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), path
+        assert "oracle/" not in text and "libvarlen_attn_oracle" not in text, path
+    for path in _sources("oracle"):
+        text = open(path).read()
+        assert not re.search(r"^\s*(from|import)\s+paper_2605_06374_amd\b", text, re.M), path
+        assert "csrc/" not in text and "libvarlen_attn.so" not in text, path
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    first = bench.index("from oracle import")
+    assert bench.index("if not args.no_cpu_baseline") < first          # only inside the baseline leg
+    assert bench.count("from oracle import") + bench.count("import oracle") == 1
