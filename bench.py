@@ -171,6 +171,19 @@ def main() -> int:
     flops = w.flops_fwd_bwd
     tflops = flops / sec_per_step / 1e12
 
+    # the same with the plan of each buffer set made once, outside the timed region, and reused
+    # by forward and backward: the other layers of a micro-batch (a context figure, not `value`)
+    for i in range(min(args.warmup, len(probs))):
+        probs[i % len(probs)].forward(reuse_plan=True)
+        probs[i % len(probs)].backward(reuse_plan=True)
+    torch.cuda.synchronize()
+    r0 = time.perf_counter()
+    for i in range(args.steps):
+        probs[i % len(probs)].forward(reuse_plan=True)
+        probs[i % len(probs)].backward(reuse_plan=True)
+    torch.cuda.synchronize()
+    reused_sec = (time.perf_counter() - r0) / args.steps
+
     # ---- per-kernel durations: same steps again, each launch bracketed by HIP events
     kernels = {}
     roofline = None
@@ -300,6 +313,8 @@ def main() -> int:
                                "above the undisturbed durations (rocprofv3 table under profiles/)",
         "sustained": sustained,
         "fwd_bwd_tflops": split_tflops,
+        "plan_reused": {"ms_per_step": round(reused_sec * 1e3, 5), "tflops": round(flops / reused_sec / 1e12, 1),
+                        "step": "fwd + bwd on a plan made beforehand (further layers of the same micro-batch)"},
         "seed": w.seed,
         "device": {"name": props.name, "cus": props.multi_processor_count},
     }

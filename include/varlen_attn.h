@@ -71,9 +71,11 @@ extern "C" {
 #define VARLEN_ATTN_STATIC_SCRATCH_BYTES (40u << 20)
 
 /* flags */
-#define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* bwd only: the workspace still holds the plan that a
-                                         preceding varlen_attn_fwd / varlen_attn_plan call
-                                         with the same params and cu_seqlens wrote */
+#define VARLEN_ATTN_FLAG_REUSE_PLAN 1 /* fwd, bwd: the workspace still holds the plan that a
+                                         preceding varlen_attn_plan / varlen_attn_fwd call with
+                                         the same params (apart from this flag) and cu_seqlens
+                                         wrote, e.g. for the other layers of the same
+                                         micro-batch; the plan step is then left out */
 #define VARLEN_ATTN_FLAG_NO_SPLIT 2   /* never cut a chain: every document is then computed
                                          exactly as if it were alone in the microbatch
                                          (bit-identical results under repacking), at the
@@ -90,6 +92,11 @@ extern "C" {
                                          to the forward call as well.  On MI355X this form is the
                                          slower one (the atomic adds bound it) and exists for
                                          comparison. */
+#define VARLEN_ATTN_FLAG_PLAN_FIRST 32 /* testing: the plan in a launch of its own in front of the forward
+                                         also on small microbatches (by default, with at most 64
+                                         documents and 256 tiles, the forward workgroups work out
+                                         their own units from cu_seqlens and the plan is made beside
+                                         them, inside the forward launch) */
 #define VARLEN_ATTN_FLAG_PLAN_LARGE 8 /* testing: plan with the general (16-wave) form of the plan kernel
                                          also where the single-wave form would be taken */
 
@@ -181,8 +188,8 @@ size_t varlen_attn_workspace_bytes(const varlen_attn_params* params);
 int varlen_attn_workspace_regions(const varlen_attn_params* params,
                                   varlen_attn_workspace_layout* out);
 
-/* Plan step alone (it is also the first step of varlen_attn_fwd and, unless
- * VARLEN_ATTN_FLAG_REUSE_PLAN is set, of varlen_attn_bwd): reads cu_seqlens on the device,
+/* Plan step alone (it is also the first step of varlen_attn_fwd and of varlen_attn_bwd unless
+ * VARLEN_ATTN_FLAG_REUSE_PLAN is set): reads cu_seqlens on the device,
  * validates it, and writes header + items into the workspace.  Integer work only. */
 int varlen_attn_plan(const varlen_attn_params* params, const int32_t* cu_seqlens,
                      void* workspace, size_t workspace_bytes, void* hip_stream);

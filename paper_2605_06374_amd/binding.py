@@ -30,6 +30,7 @@ FLAG_REUSE_PLAN = 1
 FLAG_NO_SPLIT = 2
 FLAG_PLAN_LARGE = 8
 FLAG_FUSED_BWD = 16
+FLAG_PLAN_FIRST = 32
 
 
 def flag_group_heads(n: int) -> int:

@@ -5,6 +5,7 @@
 #include "tiles.hpp"
 #include "staging.hpp"
 #include "fragments.hpp"
+#include "plan.hpp"
 
 namespace {
 
@@ -15,13 +16,13 @@ namespace {
 // normalises and stores O and LSE; otherwise it stores the unnormalised accumulator with its
 // running max and row sum for fwd_combine_kernel.
 // ----------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool SELF>
 __global__ void __launch_bounds__(kThreads, 2)
 fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
            const varlen_attn_plan_header* __restrict__ hdr,
            const varlen_attn_unit* __restrict__ units, __bf16* __restrict__ o,
            float* __restrict__ lse, float* __restrict__ partials, int N, int Hq, int Hkv,
-           float scale, int max_units) {
+           float scale, int max_units, PlanArgs plan) {
   constexpr int KK = D / 16, DB = D / 32;
   constexpr int NS = 4;                              // pipeline stages of 32 keys
   constexpr int kStageBytes = kSub * D * 2;
@@ -29,11 +30,38 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   __shared__ __attribute__((aligned(1024))) char smem[2 * NS * kStageBytes];  // K stages, V stages
 
   int unit_idx, head;
-  decode_block(blockIdx.x, Hq, unit_idx, head);
-  // both loads in flight together; the unit array always has max_units >= grid / Hq entries
-  const int n_units = hdr->n_row_units;
-  const varlen_attn_unit it = units[min(unit_idx, max_units - 1)];
-  if (unit_idx >= n_units) return;
+  varlen_attn_unit it;
+  if (SELF) {
+    // Small microbatch: no plan launch in front.  Workgroup 0 makes the plan (for the reduction
+    // of this forward and for the backward) while the others work out their own unit from
+    // cu_seqlens, in the order (tile, chunk), by the plan's rules.
+    __shared__ varlen_attn_unit own_unit;
+    __shared__ int own_valid;
+    if (blockIdx.x == 0) {
+      if (threadIdx.x < kPlanThreadsSmall) plan_body<kPlanThreadsSmall>(plan);
+      return;
+    }
+    decode_block(blockIdx.x - 1, Hq, unit_idx, head);
+    if (threadIdx.x < 64) {
+      varlen_attn_unit mine;
+      const bool ok = derive_row_unit(plan.cu, plan.B, plan.N, Hq, plan.no_split, plan.force_ch[0],
+                                      plan.slots_cap, unit_idx, threadIdx.x, mine);
+      if (threadIdx.x == 0) { own_valid = ok ? 1 : 0; if (ok) own_unit = mine; }
+    }
+    __syncthreads();
+    if (!own_valid) return;
+    // (scalar registers again: everything derived from the unit stays wave-uniform)
+    it = varlen_attn_unit{__builtin_amdgcn_readfirstlane(own_unit.row0), __builtin_amdgcn_readfirstlane(own_unit.doc_start),
+                          __builtin_amdgcn_readfirstlane(own_unit.doc_end), __builtin_amdgcn_readfirstlane(own_unit.step_begin),
+                          __builtin_amdgcn_readfirstlane(own_unit.step_end), __builtin_amdgcn_readfirstlane(own_unit.slot),
+                          __builtin_amdgcn_readfirstlane(own_unit.cost), 0};
+  } else {
+    decode_block(blockIdx.x, Hq, unit_idx, head);
+    // both loads in flight together; the unit array always has max_units >= grid / Hq entries
+    const int n_units = hdr->n_row_units;
+    it = units[min(unit_idx, max_units - 1)];
+    if (unit_idx >= n_units) return;
+  }
   const int kvh = head / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, c = lane & 31;
   const float cs = scale * kLog2e;

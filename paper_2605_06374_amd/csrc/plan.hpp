@@ -58,9 +58,114 @@ __device__ __forceinline__ int wave_inclusive_sum(int v, int lane) {
   return v;
 }
 
+// Chunk length of direction d (0: row chains, 1: column chains) from the totals of the microbatch.
+__device__ __forceinline__ int plan_chunk_steps(int d, unsigned long long steps_d, int n_tiles, int Hq,
+                                                int forced) {
+  const long long by_units = (long long)((steps_d * Hq + kTargetUnits - 1) / kTargetUnits);
+  // Units of one head ~ steps / ch + tiles / 2 (a cut chain rarely divides evenly).  If
+  // the tiles leave room, take the shortest chunks that keep every unit resident at once;
+  // dK/dV partials are twice as large and its kernel is insensitive here: twice as long.
+  const long long room = kResidentGroups / Hq - n_tiles / 2;
+  long long by_fill = 0;
+  if (room >= kResidentGroups / Hq / 4 && room > 0)
+    by_fill = (d + 1) * (((long long)steps_d + room - 1) / room);
+  const int ch = (int)max(max((long long)kMinChunkSteps, by_fill), by_units);
+  return forced > 0 ? forced : ch;
+}
+
+// sum over the lanes of a wave (all lanes get it)
+__device__ __forceinline__ int wave_total(int v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// ----------------------------------------------------------------------------------------
+// The u-th row unit of a microbatch of at most 64 documents and 256 tiles, in the order
+// (tile, chunk), worked out by one wave from cu_seqlens alone with the plan's own rules (chunk
+// length, nearly equal chunks, slots of cut tiles numbered in tile order): a forward workgroup
+// of a small microbatch finds its unit this way instead of waiting for the plan.  All 64
+// lanes must call it; every lane gets the same answer.  False: cu_seqlens is malformed (the
+// plan reports it) or u is past the last unit.
+// ----------------------------------------------------------------------------------------
+constexpr int kSelfPlanDocs = 64, kSelfPlanTiles = 256;
+__device__ __forceinline__ bool derive_row_unit(const int32_t* __restrict__ cu, int B, int N, int Hq,
+                                                int no_split, int forced, int slots_cap, int u,
+                                                int lane, varlen_attn_unit& out) {
+  int s = 0, e = 0;
+  if (lane < B) { s = cu[lane]; e = cu[lane + 1]; }
+  const int l = e - s;
+  const int cu_first = __shfl(s, 0), cu_last = __shfl(e, B - 1);
+  if (__any(lane < B && l < 0) || cu_first != 0 || cu_last != N) return false;
+  const int T = (l + kTile - 1) / kTile, S = (l + kStep - 1) / kStep;
+  const int t_incl = wave_inclusive_sum(T, lane);   // tiles up to and including this document
+  const int n_tiles = __shfl(t_incl, 63);
+  const int steps = wave_total(T * (T - 1) + S);
+  int ch = no_split ? kNoSplitSteps : plan_chunk_steps(0, (unsigned long long)steps, n_tiles, Hq, forced);
+  constexpr int kRounds = kSelfPlanTiles / 64;
+  int ds[kRounds], de[kRounds], row0[kRounds], n[kRounds], nc[kRounds];
+  // tiles 64 r + lane: their document (the first whose running tile count exceeds the tile
+  // index, found by bisection over the lanes), first row and chain length
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    ds[r] = de[r] = row0[r] = n[r] = 0;
+    if (64 * r < n_tiles) {
+      const int t = 64 * r + lane;
+      // doc = number of documents whose running tile count is <= t (it is non-decreasing over
+      // the lanes, and lane 63 holds n_tiles > t for every tile that exists)
+      int doc = 0;
+#pragma unroll
+      for (int step = 32; step >= 1; step >>= 1)
+        if (__shfl(t_incl, doc + step - 1) <= t) doc += step;
+      ds[r] = __shfl(s, doc); de[r] = __shfl(e, doc);
+      const int before = __shfl(t_incl - T, doc);
+      row0[r] = ds[r] + (t - before) * kTile;
+      n[r] = t < n_tiles ? (min(row0[r] + kTile, de[r]) - 1 - ds[r]) / kStep + 1 : 0;
+    }
+  }
+  // chunks per tile; the chunk length doubles until the chunks of cut chains fit their slots
+#pragma unroll 1
+  for (;;) {
+    int cut = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      nc[r] = n[r] ? (n[r] + ch - 1) / ch : 0;
+      cut += nc[r] > 1 ? nc[r] : 0;
+    }
+    if (no_split || wave_total(cut) <= slots_cap) break;
+    ch *= 2;
+  }
+  int units_before = 0, slots_before = 0;
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    if (64 * r < n_tiles) {
+      const int cut = nc[r] > 1 ? nc[r] : 0;
+      const int u_incl = wave_inclusive_sum(nc[r], lane), s_incl = wave_inclusive_sum(cut, lane);
+      const int u0 = units_before + u_incl - nc[r];
+      const unsigned long long hit = __ballot(u0 <= u && u < u0 + nc[r]);
+      if (hit) {
+        const int src = __ffsll((long long)hit) - 1;
+        const int nn = __shfl(n[r], src), k = __shfl(nc[r], src), c = u - __shfl(u0, src);
+        const int slot0 = slots_before + __shfl(s_incl - cut, src);
+        const int base = nn / k, rem = nn % k;
+        const int first = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
+        out = varlen_attn_unit{__shfl(row0[r], src), __shfl(ds[r], src), __shfl(de[r], src), first,
+                               first + len, k > 1 ? slot0 + c : -1, len, 0};
+        return true;
+      }
+      units_before += __shfl(u_incl, 63);
+      slots_before += __shfl(s_incl, 63);
+    }
+  }
+  return false;
+}
+
 template <int kPlanThreads>
-__global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
+__device__ __forceinline__ void plan_body(const PlanArgs& a) {
   constexpr int kPlanWaves = kPlanThreads / 64;
+  // one wave: the tiles are visited in order, so the slots of cut row chains can be numbered in
+  // tile order by a running sum (a forward workgroup that works out its own unit needs that)
+  constexpr bool kOrdered = kPlanWaves == 1;
   static_assert(2 * kPlanClasses * kPlanWaves == kPlanThreads, "one thread per class counter");
   __shared__ int doc_first_tile[kPlanThreads + 1];  // running tile count of the batch's documents
   __shared__ int doc_s[kPlanThreads], doc_e[kPlanThreads];
@@ -117,16 +222,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
   for (int d = 0; d < 2; ++d) {
     ch[d] = kNoSplitSteps;
     if (!a.no_split) {
-      const long long by_units = (long long)((steps[d] * a.Hq + kTargetUnits - 1) / kTargetUnits);
-      // Units of one head ~ steps / ch + tiles / 2 (a cut chain rarely divides evenly).  If
-      // the tiles leave room, take the shortest chunks that keep every unit resident at once;
-      // dK/dV partials are twice as large and its kernel is insensitive here: twice as long.
-      const long long room = kResidentGroups / a.Hq - n_tiles / 2;
-      long long by_fill = 0;
-      if (room >= kResidentGroups / a.Hq / 4 && room > 0)
-        by_fill = (d + 1) * (((long long)steps[d] + room - 1) / room);
-      ch[d] = (int)max(max((long long)kMinChunkSteps, by_fill), by_units);
-      if (a.force_ch[d] > 0) ch[d] = a.force_ch[d];
+      ch[d] = plan_chunk_steps(d, steps[d], n_tiles, a.Hq, a.force_ch[d]);
     }
   }
   // Grouped-query attention: a column unit may sweep several q heads of its group (their dK,
@@ -158,6 +254,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
       if (tid < 2) split[tid] = 0;
       __syncthreads();
     }
+    int row_slots_before = 0;   // cut row chains' slots so far, in tile order (single-wave form)
 #pragma unroll 1
     for (int b0 = 0; b0 < a.B; b0 += kPlanThreads) {
       // ---- this batch's documents: running tile count (exclusive) by a workgroup-wide scan
@@ -178,47 +275,66 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
         __syncthreads();
       }
       const int batch_tiles = doc_first_tile[kPlanThreads];
+      // every thread makes the same number of turns (the running sums are wave-wide scans)
 #pragma unroll 1
-      for (int t = tid; t < batch_tiles; t += kPlanThreads) {
-        // document of tile t: the last one whose first tile is <= t (documents without tiles
-        // repeat the value of their successor and are skipped by taking the last)
-        int lo = 0, hi = kPlanThreads;   // doc_first_tile[lo] <= t < doc_first_tile[hi]
+      for (int t0 = 0; t0 < batch_tiles; t0 += kPlanThreads) {
+        const int t = t0 + tid;
+        const bool valid = t < batch_tiles;
+        int ss = 0, ee = 0, row0 = 0, n_d[2] = {0, 0}, nc_d[2] = {0, 0};
+        if (valid) {
+          // document of tile t: the last one whose first tile is <= t (documents without tiles
+          // repeat the value of their successor and are skipped by taking the last)
+          int lo = 0, hi = kPlanThreads;   // doc_first_tile[lo] <= t < doc_first_tile[hi]
 #pragma unroll 1
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (doc_first_tile[mid] <= t) lo = mid; else hi = mid;
+          while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (doc_first_tile[mid] <= t) lo = mid; else hi = mid;
+          }
+          ss = doc_s[lo]; ee = doc_e[lo];
+          row0 = ss + (t - doc_first_tile[lo]) * kTile;
+          n_d[0] = (min(row0 + kTile, ee) - 1 - ss) / kStep + 1;
+          n_d[1] = (ee - row0 + kStep - 1) / kStep;
+          nc_d[0] = (n_d[0] + ch[0] - 1) / ch[0];
+          nc_d[1] = (n_d[1] + ch[1] - 1) / ch[1];
         }
-        const int ss = doc_s[lo], ee = doc_e[lo];
-        const int row0 = ss + (t - doc_first_tile[lo]) * kTile;
+        // slots of a cut row chain, numbered in tile order
+        int ordered_slot0 = 0;
+        if (kOrdered) {
+          const int cut = nc_d[0] > 1 ? nc_d[0] : 0;
+          const int incl = wave_inclusive_sum(cut, lane);
+          ordered_slot0 = row_slots_before + incl - cut;
+          row_slots_before += __shfl(incl, 63);
+        }
+        if (valid) {
 #pragma unroll
-        for (int d = 0; d < 2; ++d) {
-          const int n = d == 0 ? (min(row0 + kTile, ee) - 1 - ss) / kStep + 1
-                               : (ee - row0 + kStep - 1) / kStep;
-          const int nc = (n + ch[d] - 1) / ch[d], base = n / nc, rem = n % nc;
-          // nc - rem chunks of `base` steps, rem chunks of base + 1 (those come first in the chain)
-          int* h_lo = &hist[d][(base - 1) >> shift[d]][wave];
-          int* h_hi = &hist[d][base >> shift[d]][wave];
-          if (mode == 0) {
-            atomicAdd(h_lo, nc - rem);
-            if (rem) atomicAdd(h_hi, rem);
-            if (nc > 1) atomicAdd(&split[d], nc);
-          } else {
-            int slot0 = -1;
-            if (nc > 1 || (d == 1 && a.g > hpu)) {
-              slot0 = atomicAdd(&n_slots[d], nc);
-              const int ci = atomicAdd(&n_comb[d], 1);
-              if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
-                a.comb[d][ci] = varlen_attn_combine_item{row0, ee, slot0, nc};
-            }
-            int pos_lo = atomicAdd(h_lo, nc - rem);
-            int pos_hi = rem ? atomicAdd(h_hi, rem) : 0;
+          for (int d = 0; d < 2; ++d) {
+            const int n = n_d[d], nc = nc_d[d], base = n / nc, rem = n % nc;
+            // nc - rem chunks of `base` steps, rem chunks of base + 1 (those come first in the chain)
+            int* h_lo = &hist[d][(base - 1) >> shift[d]][wave];
+            int* h_hi = &hist[d][base >> shift[d]][wave];
+            if (mode == 0) {
+              atomicAdd(h_lo, nc - rem);
+              if (rem) atomicAdd(h_hi, rem);
+              if (nc > 1) atomicAdd(&split[d], nc);
+            } else {
+              int slot0 = -1;
+              if (nc > 1 || (d == 1 && a.g > hpu)) {
+                if (kOrdered && d == 0) { slot0 = ordered_slot0; atomicAdd(&n_slots[0], nc); }
+                else slot0 = atomicAdd(&n_slots[d], nc);
+                const int ci = atomicAdd(&n_comb[d], 1);
+                if (ci < a.max_combine && slot0 + nc <= a.max_slots[d])
+                  a.comb[d][ci] = varlen_attn_combine_item{row0, ee, slot0, nc};
+              }
+              int pos_lo = atomicAdd(h_lo, nc - rem);
+              int pos_hi = rem ? atomicAdd(h_hi, rem) : 0;
 #pragma unroll 1
-            for (int c = 0; c < nc; ++c) {
-              const int first = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
-              const int pos = c < rem ? pos_hi++ : pos_lo++;
-              if (pos < a.max_units)
-                a.units[d][pos] = varlen_attn_unit{row0, ss, ee, first, first + len,
-                                                   slot0 < 0 ? -1 : slot0 + c, len, 0};
+              for (int c = 0; c < nc; ++c) {
+                const int first = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
+                const int pos = c < rem ? pos_hi++ : pos_lo++;
+                if (pos < a.max_units)
+                  a.units[d][pos] = varlen_attn_unit{row0, ss, ee, first, first + len,
+                                                     slot0 < 0 ? -1 : slot0 + c, len, 0};
+              }
             }
           }
         }
@@ -280,6 +396,11 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
     for (int i = 0; i < 2; ++i) hdr->reserved[i] = 0;
     hdr->pairs = (int64_t)pairs;
   }
+}
+
+template <int kPlanThreads>
+__global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanArgs a) {
+  plan_body<kPlanThreads>(a);
 }
 
 }  // namespace

@@ -182,9 +182,8 @@ Regions regions_of(char* ws, const varlen_attn_workspace_layout& L) {
                  reinterpret_cast<float*>(ws + L.dq_accumulator_offset)};
 }
 
-int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
-                const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream,
-                int32_t* status_copy = nullptr) {
+PlanArgs plan_args(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
+                   const varlen_attn_workspace_layout& L, int slots_cap, int32_t* status_copy) {
   PlanArgs a;
   a.cu = cu; a.B = p->num_docs; a.N = p->total_tokens; a.Hq = p->num_q_heads;
   a.g = p->num_q_heads / p->num_kv_heads;
@@ -197,25 +196,53 @@ int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R
   a.max_units = L.max_units; a.max_combine = L.max_combine;
   a.max_slots[0] = L.max_row_slots; a.max_slots[1] = L.max_col_slots; a.slots_cap = slots_cap;
   a.status_copy = status_copy;
-  ScopedKernelTimer timer(kPlan, stream);
-  // a microbatch with few documents and tiles is planned by a single wave (lower latency)
+  return a;
+}
+
+// a microbatch with few documents and tiles is planned by a single wave (lower latency)
+inline bool small_plan(const varlen_attn_params* p) {
   const long long tiles = (long long)p->total_tokens / kTile + p->num_docs;
-  const bool small = !(p->flags & VARLEN_ATTN_FLAG_PLAN_LARGE) && p->num_docs <= 2 * kPlanThreadsSmall && tiles <= 4 * kPlanThreadsSmall;
-  if (small) plan_kernel<kPlanThreadsSmall><<<1, kPlanThreadsSmall, 0, stream>>>(a);
+  return !(p->flags & VARLEN_ATTN_FLAG_PLAN_LARGE) && p->num_docs <= 2 * kPlanThreadsSmall &&
+         tiles <= 4 * kPlanThreadsSmall;
+}
+// ... and, smaller still, needs no plan launch in front of the forward: its workgroups work out
+// their own units while one of them makes the plan (see fwd_kernel).  They take the units in
+// the order (tile, chunk), not longest first, so this is only for microbatches whose units are
+// resident all at once: the plan cuts chains to fill the 512 / Hq workgroup slots per head as
+// long as the tiles take at most three quarters of them (plan_chunk_steps), i.e. up to
+// tiles x Hq <= 768.
+inline bool self_planned_forward(const varlen_attn_params* p) {
+  const long long tiles = (long long)p->total_tokens / kTile + p->num_docs;
+  return small_plan(p) && !(p->flags & VARLEN_ATTN_FLAG_PLAN_FIRST) && p->num_docs <= kSelfPlanDocs &&
+         tiles <= kSelfPlanTiles && tiles * p->num_q_heads <= 3 * kResidentGroups / 2;
+}
+
+int launch_plan(const varlen_attn_params* p, const int32_t* cu, const Regions& R,
+                const varlen_attn_workspace_layout& L, int slots_cap, hipStream_t stream,
+                int32_t* status_copy = nullptr) {
+  const PlanArgs a = plan_args(p, cu, R, L, slots_cap, status_copy);
+  ScopedKernelTimer timer(kPlan, stream);
+  if (small_plan(p)) plan_kernel<kPlanThreadsSmall><<<1, kPlanThreadsSmall, 0, stream>>>(a);
   else plan_kernel<kPlanThreadsLarge><<<1, kPlanThreadsLarge, 0, stream>>>(a);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
+// self_plan: the forward launch makes the plan itself (no plan launch went before)
 template <int D>
 void launch_fwd(const varlen_attn_params* p, const void* q, const void* k, const void* v, void* o,
                 float* lse, const Regions& R, const varlen_attn_workspace_layout& L,
-                hipStream_t stream) {
+                hipStream_t stream, const PlanArgs* self_plan = nullptr) {
   const int N = p->total_tokens, Hq = p->num_q_heads, Hkv = p->num_kv_heads;
   {
     ScopedKernelTimer timer(kFwd, stream);
-    fwd_kernel<D><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
-        R.row_part, N, Hq, Hkv, p->softmax_scale, L.max_units);
+    if (self_plan)
+      fwd_kernel<D, true><<<dim3(grid_for(L.max_units, Hq) + 1), kThreads, 0, stream>>>(
+          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
+          R.row_part, N, Hq, Hkv, p->softmax_scale, L.max_units, *self_plan);
+    else
+      fwd_kernel<D, false><<<dim3(grid_for(L.max_units, Hq)), kThreads, 0, stream>>>(
+          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, R.hdr, R.row_units, (__bf16*)o, lse,
+          R.row_part, N, Hq, Hkv, p->softmax_scale, L.max_units, PlanArgs{});
   }
   if (!(p->flags & VARLEN_ATTN_FLAG_NO_SPLIT)) {
     ScopedKernelTimer timer(kFwdCombine, stream);
@@ -325,10 +352,19 @@ int varlen_attn_fwd(const varlen_attn_params* params, const void* q, const void*
   if (rc != VARLEN_ATTN_OK) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const Regions R = regions_of(static_cast<char*>(workspace), L);
-  rc = launch_plan(params, cu_seqlens, R, L, cap, stream);
-  if (rc != VARLEN_ATTN_OK) return rc;
-  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream);
-  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream);
+  PlanArgs self;
+  const PlanArgs* self_plan = nullptr;
+  if (!(params->flags & VARLEN_ATTN_FLAG_REUSE_PLAN)) {
+    if (self_planned_forward(params)) {
+      self = plan_args(params, cu_seqlens, R, L, cap, nullptr);
+      self_plan = &self;
+    } else {
+      rc = launch_plan(params, cu_seqlens, R, L, cap, stream);
+      if (rc != VARLEN_ATTN_OK) return rc;
+    }
+  }
+  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream, self_plan);
+  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream, self_plan);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 
@@ -354,10 +390,18 @@ int varlen_attn_fwd_static(const varlen_attn_params* params, const void* q, cons
   if (rc != VARLEN_ATTN_OK) return rc;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const Regions R = regions_of(static_cast<char*>(ws), L);
-  rc = launch_plan(params, cu_seqlens, R, L, cap, stream, plan_status);
+  PlanArgs self;
+  const PlanArgs* self_plan = nullptr;
+  if (self_planned_forward(params)) {
+    self = plan_args(params, cu_seqlens, R, L, cap, plan_status);
+    self_plan = &self;
+    rc = VARLEN_ATTN_OK;
+  } else {
+    rc = launch_plan(params, cu_seqlens, R, L, cap, stream, plan_status);
+  }
   if (rc != VARLEN_ATTN_OK) return rc;
-  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream);
-  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream);
+  if (params->head_dim == 128) launch_fwd<128>(params, q, k, v, o, lse, R, L, stream, self_plan);
+  else launch_fwd<64>(params, q, k, v, o, lse, R, L, stream, self_plan);
   return hipGetLastError() == hipSuccess ? VARLEN_ATTN_OK : VARLEN_ATTN_LAUNCH_FAILED;
 }
 

@@ -54,8 +54,12 @@ class DeviceProblem:
     def plan(self, stream=None):
         binding.check(binding.varlen_attn_plan(self.params, self.cu, self.workspace, stream=stream))
 
-    def forward(self, stream=None):
-        binding.check(binding.varlen_attn_fwd(self.params, self.q, self.k, self.v, self.cu, self.o,
+    def forward(self, stream=None, reuse_plan=False):
+        p = self.params
+        if reuse_plan:
+            p = binding.make_params(p.total_tokens, p.num_docs, p.num_q_heads, p.num_kv_heads,
+                                    p.head_dim, p.softmax_scale, p.flags | binding.FLAG_REUSE_PLAN)
+        binding.check(binding.varlen_attn_fwd(p, self.q, self.k, self.v, self.cu, self.o,
                                               self.lse, self.workspace, stream=stream))
 
     def backward(self, stream=None, reuse_plan=False):

@@ -422,6 +422,45 @@ def test_bit_reproducible(gpu):
         assert np.array_equal(a[n], b[n]), n
 
 
+@pytest.mark.parametrize("lengths,hq,hkv,d", [SMALL[3], SMALL[6], SMALL[7], SMALL[10], SMALL[11], SMALL[13],
+                                               ([900, 130, 1500, 64, 1, 0, 700], 4, 2, 128),
+                                               ([8192], 2, 2, 64), ([3] * 64, 2, 1, 128),
+                                               ([16384 + 77], 1, 1, 128)])
+def test_self_planned_forward_equals_planned_forward(gpu, lengths, hq, hkv, d):
+    """On small microbatches the forward workgroups work out their units themselves while one of
+    them writes the plan: same units, same slots, hence the bits of a forward behind a plan
+    launch, and the same plan tables (the reduction's items in any order)."""
+    from paper_2605_06374_amd import binding
+    w = W.custom("self", lengths, hq, hkv, d, seed=sum(lengths) + 7 * hq + d)
+    a = run_all(gpu, w, flags=binding.FLAG_PLAN_FIRST)
+    b = run_all(gpu, w)
+    abits, bbits = a.result_bits(), b.result_bits()
+    for n in abits:
+        assert np.array_equal(abits[n], bbits[n]), n
+    pa, pb = a.read_plan(), b.read_plan()
+    for f, _ in pa["header"]._fields_:
+        if f != "reserved":
+            assert getattr(pa["header"], f) == getattr(pb["header"], f), f
+    for name in ("row_units", "col_units", "row_combine", "col_combine"):
+        assert sorted(map(tuple, pa[name].tolist())) == sorted(map(tuple, pb[name].tolist())), name
+    assert_close_full(b.results(), oracle_full(w), label="self-planned " + str(lengths[:6]))
+
+
+def test_forward_reuses_a_plan(gpu):
+    """One plan for the attention calls of all layers of a micro-batch: a forward that reuses the
+    plan of varlen_attn_plan gives the bits of a forward that plans itself."""
+    w = W.custom("layers", [700, 40, 1300, 5, 129], 4, 2, 128, seed=31)
+    fresh = run_all(gpu, w).result_bits()
+    prob = gpu.DeviceProblem(w)
+    prob.poison_outputs()
+    prob.plan()
+    prob.forward(reuse_plan=True)
+    prob.backward(reuse_plan=True)
+    got = prob.result_bits()
+    for n in fresh:
+        assert np.array_equal(fresh[n], got[n]), n
+
+
 def test_bwd_plans_itself_without_reuse_flag(gpu):
     from paper_2605_06374_amd import binding
     w = W.custom("noreuse", [500, 77], 2, 2, 128, seed=21)
