@@ -425,7 +425,9 @@ def test_bit_reproducible(gpu):
 @pytest.mark.parametrize("lengths,hq,hkv,d", [SMALL[3], SMALL[6], SMALL[7], SMALL[10], SMALL[11], SMALL[13],
                                                ([900, 130, 1500, 64, 1, 0, 700], 4, 2, 128),
                                                ([8192], 2, 2, 64), ([3] * 64, 2, 1, 128),
-                                               ([16384 + 77], 1, 1, 128)])
+                                               ([16384 + 77], 1, 1, 128),
+                                               ([31000, 1, 900], 2, 2, 64),          # 251 tiles: four rounds of 64
+                                               ([0, 5, 0, 0, 300, 0] + [1, 130, 64, 0] * 14 + [0, 0], 3, 1, 128)])
 def test_self_planned_forward_equals_planned_forward(gpu, lengths, hq, hkv, d):
     """On small microbatches the forward workgroups work out their units themselves while one of
     them writes the plan: same units, same slots, hence the bits of a forward behind a plan
