@@ -48,14 +48,25 @@ struct PlanArgs {
   int32_t* status_copy;   // optional second place for the status word (device), or null
 };
 
-// inclusive sum over the lanes of a wave
-__device__ __forceinline__ int wave_inclusive_sum(int v, int lane) {
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(v, off);
-    if (lane >= off) v += o;
-  }
+// inclusive sum over the lanes of a wave: data-parallel-primitive moves (shifts inside rows of
+// 16 lanes, then the last lane of a row broadcast into the rows behind it), which cost a vector
+// instruction each where a shuffle goes through the LDS crossbar and back
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ int dpp_or_zero(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, kCtrl, kRowMask, 0xF, false);
+}
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+  v += dpp_or_zero<0x111, 0xF>(v);   // row_shr:1
+  v += dpp_or_zero<0x112, 0xF>(v);   // row_shr:2
+  v += dpp_or_zero<0x114, 0xF>(v);   // row_shr:4
+  v += dpp_or_zero<0x118, 0xF>(v);   // row_shr:8
+  v += dpp_or_zero<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_or_zero<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
   return v;
+}
+// value of lane `src` (wave-uniform) in every lane
+__device__ __forceinline__ int lane_value(int v, int src) {
+  return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src));
 }
 
 // Chunk length of direction d (0: row chains, 1: column chains) from the totals of the microbatch.
@@ -74,11 +85,7 @@ __device__ __forceinline__ int plan_chunk_steps(int d, unsigned long long steps_
 }
 
 // sum over the lanes of a wave (all lanes get it)
-__device__ __forceinline__ int wave_total(int v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
+__device__ __forceinline__ int wave_total(int v) { return lane_value(wave_inclusive_sum(v), 63); }
 
 // ----------------------------------------------------------------------------------------
 // The u-th row unit of a microbatch of at most 64 documents and 256 tiles, in the order
@@ -95,11 +102,11 @@ __device__ __forceinline__ bool derive_row_unit(const int32_t* __restrict__ cu, 
   int s = 0, e = 0;
   if (lane < B) { s = cu[lane]; e = cu[lane + 1]; }
   const int l = e - s;
-  const int cu_first = __shfl(s, 0), cu_last = __shfl(e, B - 1);
+  const int cu_first = lane_value(s, 0), cu_last = lane_value(e, B - 1);
   if (__any(lane < B && l < 0) || cu_first != 0 || cu_last != N) return false;
   const int T = (l + kTile - 1) / kTile, S = (l + kStep - 1) / kStep;
-  const int t_incl = wave_inclusive_sum(T, lane);   // tiles up to and including this document
-  const int n_tiles = __shfl(t_incl, 63);
+  const int t_incl = wave_inclusive_sum(T);   // tiles up to and including this document
+  const int n_tiles = lane_value(t_incl, 63);
   const int steps = wave_total(T * (T - 1) + S);
   int ch = no_split ? kNoSplitSteps : plan_chunk_steps(0, (unsigned long long)steps, n_tiles, Hq, forced);
   constexpr int kRounds = kSelfPlanTiles / 64;
@@ -140,21 +147,21 @@ __device__ __forceinline__ bool derive_row_unit(const int32_t* __restrict__ cu, 
   for (int r = 0; r < kRounds; ++r) {
     if (64 * r < n_tiles) {
       const int cut = nc[r] > 1 ? nc[r] : 0;
-      const int u_incl = wave_inclusive_sum(nc[r], lane), s_incl = wave_inclusive_sum(cut, lane);
+      const int u_incl = wave_inclusive_sum(nc[r]), s_incl = wave_inclusive_sum(cut);
       const int u0 = units_before + u_incl - nc[r];
       const unsigned long long hit = __ballot(u0 <= u && u < u0 + nc[r]);
       if (hit) {
         const int src = __ffsll((long long)hit) - 1;
-        const int nn = __shfl(n[r], src), k = __shfl(nc[r], src), c = u - __shfl(u0, src);
-        const int slot0 = slots_before + __shfl(s_incl - cut, src);
+        const int nn = lane_value(n[r], src), k = lane_value(nc[r], src), c = u - lane_value(u0, src);
+        const int slot0 = slots_before + lane_value(s_incl - cut, src);
         const int base = nn / k, rem = nn % k;
         const int first = c * base + min(c, rem), len = base + (c < rem ? 1 : 0);
-        out = varlen_attn_unit{__shfl(row0[r], src), __shfl(ds[r], src), __shfl(de[r], src), first,
+        out = varlen_attn_unit{lane_value(row0[r], src), lane_value(ds[r], src), lane_value(de[r], src), first,
                                first + len, k > 1 ? slot0 + c : -1, len, 0};
         return true;
       }
-      units_before += __shfl(u_incl, 63);
-      slots_before += __shfl(s_incl, 63);
+      units_before += lane_value(u_incl, 63);
+      slots_before += lane_value(s_incl, 63);
     }
   }
   return false;
@@ -263,7 +270,7 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
         int s = 0, e = 0;
         if (b < a.B) { s = cu[b]; e = cu[b + 1]; }
         const int T = (e - s + kTile - 1) / kTile;
-        const int incl = wave_inclusive_sum(T, lane);
+        const int incl = wave_inclusive_sum(T);
         if (lane == 63) wave_sum[wave] = incl;
         doc_s[tid] = s; doc_e[tid] = e;
         __syncthreads();
@@ -301,9 +308,9 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
         int ordered_slot0 = 0;
         if (kOrdered) {
           const int cut = nc_d[0] > 1 ? nc_d[0] : 0;
-          const int incl = wave_inclusive_sum(cut, lane);
+          const int incl = wave_inclusive_sum(cut);
           ordered_slot0 = row_slots_before + incl - cut;
-          row_slots_before += __shfl(incl, 63);
+          row_slots_before += lane_value(incl, 63);
         }
         if (valid) {
 #pragma unroll
